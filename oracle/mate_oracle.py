@@ -1,0 +1,186 @@
+"""CPU oracle for MATE multi-view sparse attention.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this file.
+It shares no code with the HIP library and never calls it.  Everything is float64 numpy,
+written as the plain definition: an explicit N x N 0/1 mask, a dense masked softmax, and
+the textbook derivative of that.  There is no tiling, sorting trick, online softmax or
+fusion here; `numpy.matmul`, `numpy.exp` and `sorted` are the only library steps.
+
+What each function follows in the paper (arXiv 2109.04312):
+  * attention_mask      -- the attention-pattern equation of Section 3 (the three-case
+                           definition of A^i_k), with "all positions (except padding)".
+  * attn_forward        -- the head equation of Section 3 (gather over A^i_k, softmax of
+                           key.query scores, weighted sum of values), realised as the
+                           mask-based implementation the same section describes.
+  * attn_backward       -- not in the paper: the derivative of attn_forward w.r.t. Q, K, V.
+  * build_segments      -- the per-head data-dependent, deterministic reordering of
+                           Section 3.1 (row-order / column-order traversal), stated as a
+                           stable sort plus run boundaries.
+
+Readings taken where the paper is silent (listed again in the design notes):
+  * the softmax scale is an explicit argument (the equation has none, the appendix
+    listing divides by sqrt(head size));
+  * Q is given by a per-token GLOBAL flag, not inferred from row = column = 0;
+  * a table token with id 0 shares a segment only with other *table* tokens of id 0;
+  * padding is a third flag value: pad keys get exactly zero weight, pad queries
+    produce zero output and zero gradients;
+  * local rows use ONE softmax over (global keys U own row/column keys).
+
+Pins: tests/test_oracle_*.py (brute force from set notation, library SDPA special
+cases, closed forms, finite differences, permutation / relabelling invariants,
+brute-force ranks for the segment tables).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+TOK_LOCAL, TOK_GLOBAL, TOK_PAD = 0, 1, 2
+HEAD_ROW, HEAD_COL = 0, 1
+
+
+# --------------------------------------------------------------------------------------
+# Attention pattern (Section 3, definition of A^i_k)
+# --------------------------------------------------------------------------------------
+def attention_mask(row_ids, col_ids, flags, kind) -> np.ndarray:
+    """mask[k, j] = 1 iff query position k may attend to key position j (one sequence).
+
+    k in Q (GLOBAL)  -> every non-pad j
+    else, row head   -> Q  U  {j : r_j = r_k}
+    else, column head-> Q  U  {j : c_j = c_k}
+    Pad keys are never attended; pad queries attend to nothing.  The sets {j : r_j = r_k}
+    range over table tokens only (a question token enters once, through Q).
+    """
+    row_ids = np.asarray(row_ids)
+    col_ids = np.asarray(col_ids)
+    flags = np.asarray(flags)
+    ids = row_ids if kind == HEAD_ROW else col_ids
+    is_g = flags == TOK_GLOBAL
+    is_l = flags == TOK_LOCAL
+    nonpad = is_g | is_l
+    same = (ids[:, None] == ids[None, :]) & is_l[:, None] & is_l[None, :]
+    m = same | (is_g[:, None] & nonpad[None, :]) | (is_l[:, None] & is_g[None, :])
+    return m.astype(np.uint8)
+
+
+def useful_pairs(row_ids, col_ids, flags, kind) -> int:
+    """Number of (query, key) pairs with non-zero weight for one sequence and head kind."""
+    return int(attention_mask(row_ids, col_ids, flags, kind).sum(dtype=np.int64))
+
+
+# --------------------------------------------------------------------------------------
+# Forward (Section 3, head equation; mask-based implementation)
+# --------------------------------------------------------------------------------------
+def _head_forward(q, k, v, mask, scale):
+    """One (sequence, head): q,k,v [N,D] float64, mask [N,N] -> O [N,D], LSE [N], P [N,N]."""
+    s = scale * (q @ k.T)
+    allowed = mask.astype(bool)
+    has = allowed.any(axis=1)
+    s_m = np.where(allowed, s, -np.inf)
+    m = np.where(has, s_m.max(axis=1, initial=-np.inf), 0.0)
+    e = np.where(allowed, np.exp(s_m - m[:, None]), 0.0)
+    z = e.sum(axis=1)
+    p = e / np.where(has, z, 1.0)[:, None]
+    o = p @ v
+    lse = np.where(has, m + np.log(np.where(has, z, 1.0)), 0.0)
+    return o, lse, p
+
+
+def attn_forward(q, k, v, row_ids, col_ids, flags, head_kind, scale):
+    """q,k,v [B,H,N,D] -> (O [B,H,N,D] float64, LSE [B,H,N] float64).
+
+    LSE_k = log sum_{j in A_k} exp(scale * q_k.k_j); rows of pad queries are 0 in both.
+    """
+    q = np.asarray(q, np.float64)
+    k = np.asarray(k, np.float64)
+    v = np.asarray(v, np.float64)
+    B, H, N, D = q.shape
+    o = np.zeros((B, H, N, D), np.float64)
+    lse = np.zeros((B, H, N), np.float64)
+    for b in range(B):
+        masks = {}
+        for h in range(H):
+            kind = int(head_kind[h])
+            if kind not in masks:
+                masks[kind] = attention_mask(row_ids[b], col_ids[b], flags[b], kind)
+            o[b, h], lse[b, h], _ = _head_forward(q[b, h], k[b, h], v[b, h], masks[kind], scale)
+    return o, lse
+
+
+# --------------------------------------------------------------------------------------
+# Backward (derivative of the above; loss gradient dO is the only incoming gradient)
+# --------------------------------------------------------------------------------------
+def _head_backward(q, k, v, do, mask, scale):
+    o, _, p = _head_forward(q, k, v, mask, scale)
+    delta = (do * o).sum(axis=1)             # delta_k = dO_k . O_k
+    dv = p.T @ do                            # dV_j = sum_k P[k,j] dO_k
+    dp = do @ v.T                            # dP[k,j] = dO_k . V_j
+    ds = p * (dp - delta[:, None])           # softmax Jacobian, row by row
+    dq = scale * (ds @ k)                    # dQ_k = scale sum_j dS[k,j] K_j
+    dk = scale * (ds.T @ q)                  # dK_j = scale sum_k dS[k,j] Q_k
+    return dq, dk, dv
+
+
+def attn_backward(q, k, v, do, row_ids, col_ids, flags, head_kind, scale):
+    """Gradients (dQ, dK, dV) [B,H,N,D] float64 of sum(O * dO); dO at pad queries is ignored."""
+    q = np.asarray(q, np.float64)
+    k = np.asarray(k, np.float64)
+    v = np.asarray(v, np.float64)
+    do = np.asarray(do, np.float64)
+    B, H, N, D = q.shape
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(q)
+    dv = np.zeros_like(q)
+    for b in range(B):
+        masks = {}
+        nonpad = (np.asarray(flags[b]) != TOK_PAD)[:, None]
+        for h in range(H):
+            kind = int(head_kind[h])
+            if kind not in masks:
+                masks[kind] = attention_mask(row_ids[b], col_ids[b], flags[b], kind)
+            dq[b, h], dk[b, h], dv[b, h] = _head_backward(
+                q[b, h], k[b, h], v[b, h], do[b, h] * nonpad, masks[kind], scale)
+    return dq, dk, dv
+
+
+# --------------------------------------------------------------------------------------
+# Segment tables (Section 3.1: per-head reordering of the table tokens)
+# --------------------------------------------------------------------------------------
+def build_segments(row_ids, col_ids, flags):
+    """Per-sequence integer tables, fixed-size arrays filled with -1 past their valid length.
+
+    Returns a dict with
+      counts      [B,4]  int32 : G (global), L (table), S_row, S_col
+      global_idx  [B,N]  int32 : ascending positions of GLOBAL tokens
+      perm        [2,B,N]  int32 : view 0 = rows, 1 = columns; table-token positions sorted by
+                                   (id, position) -- i.e. a stable sort by id
+      seg_off     [2,B,N+1] int32: first sorted slot of each segment, then L
+      seg_of_tok  [2,B,N]  int32 : segment index of each table token, -1 for others
+    """
+    row_ids = np.asarray(row_ids)
+    col_ids = np.asarray(col_ids)
+    flags = np.asarray(flags)
+    B, N = flags.shape
+    counts = np.zeros((B, 4), np.int32)
+    global_idx = np.full((B, N), -1, np.int32)
+    perm = np.full((2, B, N), -1, np.int32)
+    seg_off = np.full((2, B, N + 1), -1, np.int32)
+    seg_of_tok = np.full((2, B, N), -1, np.int32)
+    for b in range(B):
+        glob = [p for p in range(N) if flags[b, p] == TOK_GLOBAL]
+        loc = [p for p in range(N) if flags[b, p] == TOK_LOCAL]
+        counts[b, 0] = len(glob)
+        counts[b, 1] = len(loc)
+        global_idx[b, : len(glob)] = glob
+        for view, ids in enumerate((row_ids[b], col_ids[b])):
+            order = sorted(loc, key=lambda p: int(ids[p]))   # Python's sort is stable
+            perm[view, b, : len(order)] = order
+            n_seg = 0
+            for slot, p in enumerate(order):
+                if slot == 0 or ids[p] != ids[order[slot - 1]]:
+                    seg_off[view, b, n_seg] = slot
+                    n_seg += 1
+                seg_of_tok[view, b, p] = n_seg - 1
+            seg_off[view, b, n_seg] = len(order)
+            counts[b, 2 + view] = n_seg
+    return dict(counts=counts, global_idx=global_idx, perm=perm, seg_off=seg_off,
+                seg_of_tok=seg_of_tok)
