@@ -1,0 +1,153 @@
+/*
+ * mate.h -- C ABI of the MI355X (gfx950) implementation of MATE multi-view sparse
+ * self-attention (arXiv 2109.04312, "MATE: Multi-view Attention for Table Transformer
+ * Efficiency").
+ *
+ * The operation (Section 3 of the paper).  Every token k of a sequence carries a row
+ * number r_k and a column number c_k, and is either a table token, a question token
+ * (member of the set Q; attends to and from everything) or padding.  Head i of kind ROW
+ * lets table token k attend to  Q U {j : r_j = r_k};  a head of kind COLUMN to
+ * Q U {j : c_j = c_k};  a question token attends to every non-pad token (the three-case
+ * definition of the attention pattern A^i_k).  The output at position k is the softmax
+ * over A^i_k of scale * q_k . k_j applied to the values v_j (the head equation of the same
+ * section, after the Q/K/V projections).  The result equals the mask-based implementation
+ * exactly; it is computed the way Section 3.1 proposes -- each head kind reorders the table
+ * tokens (row order / column order) so that its keys are contiguous -- but with exact
+ * variable-length segments in place of fixed-radius buckets.
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers unless the comment says HOST.  The caller owns every
+ *     buffer (inputs, outputs, segment tables, workspace); the library allocates nothing
+ *     and keeps no state between calls.
+ *   - Tensors are contiguous, row-major.  Q, K, V, O, dO, dQ, dK, dV are [B, H, N, D];
+ *     LSE is [B, H, N] float; row_ids / col_ids are [B, N] int32; flags is [B, N] uint8.
+ *   - D must be 64.  1 <= N <= MATE_MAX_N.  1 <= H <= MATE_MAX_HEADS.  B >= 1.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; only the calls documented as synchronising wait for it.
+ *   - Return value: MATE_OK or a negative mate_status.  Argument errors are detected on the
+ *     host before anything is launched; nothing is written in that case.
+ *   - Base pointers must be 16-byte aligned (any hipMalloc / torch allocation is).
+ */
+#ifndef MATE_H_
+#define MATE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MATE_OK = 0,
+  MATE_ERR_NULL = -1,        /* a required pointer is NULL                                */
+  MATE_ERR_SHAPE = -2,       /* B, H, N out of range, or tables built for another (B, N)  */
+  MATE_ERR_UNSUPPORTED = -3, /* D != 64, unknown dtype, unknown head kind                 */
+  MATE_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than mate_workspace_bytes(...)    */
+  MATE_ERR_BAD_ID = -5,      /* a table token has a negative id, or a flag value > 2      */
+  MATE_ERR_HIP = -6          /* a HIP call or kernel launch failed                        */
+} mate_status;
+
+typedef enum { MATE_F32 = 0, MATE_BF16 = 1 } mate_dtype;
+
+/* flags[b, n]: what kind of token sits at position n */
+enum { MATE_TOK_LOCAL = 0, MATE_TOK_GLOBAL = 1, MATE_TOK_PAD = 2 };
+/* head_kind[h] */
+enum { MATE_HEAD_ROW = 0, MATE_HEAD_COL = 1 };
+
+enum { MATE_MAX_N = 16384, MATE_MAX_HEADS = 256, MATE_HEAD_DIM = 64 };
+
+/* Device bytes needed for the segment tables of B sequences of length N (0 if out of range). */
+size_t mate_segments_bytes(int B, int N);
+
+/* Device bytes of scratch needed by mate_attn_fwd (for_bwd = 0) or mate_attn_bwd
+ * (for_bwd = 1) for this shape; may be 0.  The contents need no initialisation and are
+ * undefined afterwards. */
+size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bwd);
+
+/*
+ * Segment builder -- the data-dependent but deterministic per-head-kind reordering of
+ * Section 3.1 ("row order traversal" / "column order traversal"), which the paper notes can
+ * be computed once per input (caption of the complexity table).  Integer work only.
+ *
+ * For every sequence b it classifies positions by flag, lists GLOBAL positions in ascending
+ * order, and for each view (0 = rows, 1 = columns) stable-sorts the LOCAL positions by their
+ * id (row_ids for view 0, col_ids for view 1; ties keep ascending position), numbers the
+ * runs of equal id 0..S-1 ("segments") and records where each run starts.  Ids of GLOBAL
+ * and PAD tokens are ignored.  A LOCAL token with id 0 shares a segment only with other
+ * LOCAL tokens of id 0.
+ *
+ *   row_ids, col_ids  [B, N] int32, >= 0 for LOCAL tokens
+ *   flags             [B, N] uint8, MATE_TOK_*
+ *   segments          mate_segments_bytes(B, N) bytes, overwritten entirely
+ *
+ * Asynchronous on `stream`.  A negative id on a LOCAL token or a flag > 2 does not stop the
+ * build (the id is ordered as an unsigned number, the token is treated as padding) but sets
+ * a status word that mate_segments_export reports as MATE_ERR_BAD_ID.
+ */
+mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, int B, int N, void* segments,
+                                void* stream);
+
+/*
+ * Copies the tables of one view to HOST arrays (test and inspection hook; waits for
+ * `stream`).  Any output pointer may be NULL.  Entries past the valid length are -1.
+ *
+ *   perm        HOST [B, N]    sorted slot -> token position, first L_b valid
+ *   seg_off     HOST [B, N+1]  first slot of segment i, then L_b at index S_b
+ *   seg_of_tok  HOST [B, N]    token position -> segment index, -1 for GLOBAL / PAD
+ *   global_idx  HOST [B, N]    ascending GLOBAL positions, first G_b valid
+ *   counts      HOST [B, 3]    G_b, L_b, S_b (of this view)
+ *
+ * Returns MATE_ERR_BAD_ID if the builder met an invalid id or flag, MATE_ERR_SHAPE if the
+ * buffer was built for another (B, N).
+ */
+mate_status mate_segments_export(const void* segments, int B, int N, int view, int32_t* perm,
+                                 int32_t* seg_off, int32_t* seg_of_tok, int32_t* global_idx,
+                                 int32_t* counts, void* stream);
+
+/*
+ * Forward pass: O[b,h,k,:] = sum_{j in A} softmax_j(scale * q_k . k_j) v_j with A the
+ * attention pattern of Section 3 for head kind head_kind[h]; one softmax over the union
+ * of question keys and own-row (own-column) keys.  LSE[b,h,k] = log sum_{j in A}
+ * exp(scale * q_k . k_j), kept for the backward pass.  PAD positions get O = 0, LSE = 0.
+ *
+ *   q, k, v     [B, H, N, D] of dtype t (bf16: accumulate and softmax in fp32, probabilities
+ *               rounded to bf16 before multiplying V; f32: fp32 throughout)
+ *   segments    tables from mate_build_segments for the same (B, N)
+ *   head_kind   HOST [H] uint8, MATE_HEAD_*
+ *   scale       softmax scale (the appendix listing uses 1/sqrt(D))
+ *   out         [B, H, N, D] dtype t;  lse [B, H, N] float
+ *   workspace   mate_workspace_bytes(..., 0) bytes (may be NULL if that is 0)
+ *
+ * Asynchronous on `stream`.  Does not read the builder's status word.
+ */
+mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const void* segments,
+                          const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
+                          float scale, void* out, float* lse, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
+ * Backward pass: gradients of sum(O * dO) with respect to Q, K, V (the derivative of the
+ * forward above; the paper trains through it but does not write it out).  `out` and `lse`
+ * are the forward's results for the same inputs.  dO at PAD positions is ignored; PAD
+ * positions of dq, dk, dv are written 0.  Deterministic: no floating-point atomics, two
+ * runs give identical bits.
+ *
+ *   dout        [B, H, N, D] dtype t
+ *   dq, dk, dv  [B, H, N, D] dtype t (overwritten)
+ *   workspace   mate_workspace_bytes(..., 1) bytes
+ */
+mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                          const float* lse, const void* dout, const void* segments,
+                          const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
+                          float scale, void* dq, void* dk, void* dv, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code (HOST pointer, never NULL). */
+const char* mate_status_string(mate_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MATE_H_ */

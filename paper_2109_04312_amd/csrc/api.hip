@@ -1,0 +1,148 @@
+// C ABI entry points: argument validation on the host, then kernel launches on the caller's
+// stream.  No allocation, no global state.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <vector>
+
+#include "../../include/mate.h"
+#include "launch.h"
+#include "seg_layout.h"
+
+using namespace mate;
+
+namespace {
+
+bool shape_ok(int B, int N) { return B >= 1 && N >= 1 && N <= MATE_MAX_N; }
+
+size_t delta_bytes(int B, int H, int N) { return (size_t)B * H * N * sizeof(float); }
+
+mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kind, int B, int H,
+                      int N, int D, mate_dtype t, float scale) {
+  if (!segments || !head_kind) return MATE_ERR_NULL;
+  if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS) return MATE_ERR_SHAPE;
+  if (D != MATE_HEAD_DIM || (t != MATE_F32 && t != MATE_BF16)) return MATE_ERR_UNSUPPORTED;
+  std::memset(&a, 0, sizeof(a));
+  for (int h = 0; h < H; ++h) {
+    if (head_kind[h] > MATE_HEAD_COL) return MATE_ERR_UNSUPPORTED;
+    a.head_kind[h] = head_kind[h];
+  }
+  a.seg = make_tables(segments, B, N);
+  a.B = B;
+  a.H = H;
+  a.N = N;
+  a.scale = scale;
+  return MATE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mate_segments_bytes(int B, int N) {
+  if (!shape_ok(B, N)) return 0;
+  return SegLayout(B, N).total * sizeof(int);
+}
+
+size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bwd) {
+  (void)t;
+  if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS || D != MATE_HEAD_DIM) return 0;
+  return for_bwd ? delta_bytes(B, H, N) : 0;
+}
+
+mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, int B, int N, void* segments,
+                                void* stream) {
+  if (!row_ids || !col_ids || !flags || !segments) return MATE_ERR_NULL;
+  if (!shape_ok(B, N)) return MATE_ERR_SHAPE;
+  hipError_t e = launch_build_segments(row_ids, col_ids, flags, B, N,
+                                       static_cast<int*>(segments),
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_segments_export(const void* segments, int B, int N, int view, int32_t* perm,
+                                 int32_t* seg_off, int32_t* seg_of_tok, int32_t* global_idx,
+                                 int32_t* counts, void* stream) {
+  if (!segments) return MATE_ERR_NULL;
+  if (!shape_ok(B, N) || view < 0 || view > 1) return MATE_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const SegLayout lay(B, N);
+  const int* w = static_cast<const int*>(segments);
+  const int* vb = w + lay.view0 + (size_t)view * lay.view_stride;
+  std::vector<int> head(kHdrWords + (size_t)B * kCountWords);
+#define MATE_D2H(dst, src, words)                                                             \
+  if (hipMemcpyAsync(dst, src, (size_t)(words) * sizeof(int), hipMemcpyDeviceToHost, s) !=    \
+      hipSuccess)                                                                             \
+    return MATE_ERR_HIP;
+  MATE_D2H(head.data(), w, head.size());
+  if (perm) MATE_D2H(perm, vb + lay.perm, (size_t)B * N);
+  if (seg_off) MATE_D2H(seg_off, vb + lay.seg_off, (size_t)B * (N + 1));
+  if (seg_of_tok) MATE_D2H(seg_of_tok, vb + lay.seg_of_tok, (size_t)B * N);
+  if (global_idx) MATE_D2H(global_idx, w + lay.global_idx, (size_t)B * N);
+#undef MATE_D2H
+  if (hipStreamSynchronize(s) != hipSuccess) return MATE_ERR_HIP;
+  if (head[0] != kMagic || head[1] != B || head[2] != N) return MATE_ERR_SHAPE;
+  int bad = 0;
+  for (int b = 0; b < B; ++b) {
+    const int* c = head.data() + kHdrWords + (size_t)b * kCountWords;
+    if (counts) {
+      counts[3 * b + 0] = c[C_G];
+      counts[3 * b + 1] = c[C_L];
+      counts[3 * b + 2] = c[C_SROW + view];
+    }
+    bad |= c[5] | c[6];
+  }
+  return bad ? MATE_ERR_BAD_ID : MATE_OK;
+}
+
+mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const void* segments,
+                          const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
+                          float scale, void* out, float* lse, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !out || !lse) return MATE_ERR_NULL;
+  AttnArgs a;
+  mate_status st = fill_args(a, segments, head_kind, B, H, N, D, t, scale);
+  if (st != MATE_OK) return st;
+  const size_t need = mate_workspace_bytes(B, H, N, D, t, 0);
+  if (need && (!workspace || workspace_bytes < need)) return MATE_ERR_WORKSPACE;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = (t == MATE_BF16) ? launch_fwd_mfma(a, s) : launch_fwd_scalar(a, false, s);
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                          const float* lse, const void* dout, const void* segments,
+                          const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
+                          float scale, void* dq, void* dk, void* dv, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return MATE_ERR_NULL;
+  AttnArgs a;
+  mate_status st = fill_args(a, segments, head_kind, B, H, N, D, t, scale);
+  if (st != MATE_OK) return st;
+  const size_t need = mate_workspace_bytes(B, H, N, D, t, 1);
+  if (need && (!workspace || workspace_bytes < need)) return MATE_ERR_WORKSPACE;
+  a.q = q; a.k = k; a.v = v; a.o = out; a.dout = dout;
+  a.lse = const_cast<float*>(lse);
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.delta = static_cast<float*>(workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = (t == MATE_BF16) ? launch_bwd_mfma(a, s) : launch_bwd_scalar(a, false, s);
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+const char* mate_status_string(mate_status s) {
+  switch (s) {
+    case MATE_OK: return "ok";
+    case MATE_ERR_NULL: return "a required pointer is NULL";
+    case MATE_ERR_SHAPE: return "shape out of range, or segment tables built for another (B, N)";
+    case MATE_ERR_UNSUPPORTED: return "unsupported head size, dtype or head kind";
+    case MATE_ERR_WORKSPACE: return "workspace too small";
+    case MATE_ERR_BAD_ID: return "negative id on a table token, or flag value above 2";
+    case MATE_ERR_HIP: return "HIP call or kernel launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

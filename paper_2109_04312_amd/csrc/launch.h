@@ -1,0 +1,35 @@
+// Host-side launchers, one per kernel family.  Everything is enqueued on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "seg_layout.h"
+
+namespace mate {
+
+struct AttnArgs {
+  const void *q, *k, *v;    // [B,H,N,64]
+  const void *o, *dout;     // backward only
+  void *out;                // forward only
+  float* lse;               // forward: written; backward: read (const in spirit)
+  void *dq, *dk, *dv;       // backward only
+  float* delta;             // backward scratch [B,H,N]
+  SegTables seg;
+  unsigned char head_kind[256];
+  int B, H, N;
+  float scale;
+};
+
+hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
+                                 const unsigned char* flags, int B, int N, int* seg,
+                                 hipStream_t stream);
+
+// Scalar (non-MFMA) kernels: fp32 arithmetic throughout, one wavefront per query / key.
+// They serve dtype f32 and are the fallback-free reference-quality path for it.
+hipError_t launch_fwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
+hipError_t launch_bwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
+
+// bf16 MFMA kernels.
+hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream);
+hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace mate

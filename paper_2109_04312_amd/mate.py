@@ -1,0 +1,176 @@
+"""ctypes binding over libmate.so (the C ABI of include/mate.h).  Argument marshalling only.
+
+The raw entry points are exposed under their C names (`mate_build_segments`, ...) taking
+integer addresses; the snake-case helpers below take torch tensors, allocate outputs with
+torch (device memory + current stream are all torch is used for) and raise on any non-zero
+status.  There is no fallback: if the library is missing this module raises on import.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmate.so")
+
+MATE_OK = 0
+MATE_ERR_NULL, MATE_ERR_SHAPE, MATE_ERR_UNSUPPORTED = -1, -2, -3
+MATE_ERR_WORKSPACE, MATE_ERR_BAD_ID, MATE_ERR_HIP = -4, -5, -6
+MATE_F32, MATE_BF16 = 0, 1
+MATE_TOK_LOCAL, MATE_TOK_GLOBAL, MATE_TOK_PAD = 0, 1, 2
+MATE_HEAD_ROW, MATE_HEAD_COL = 0, 1
+MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
+
+EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
+           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_status_string"]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2109_04312_amd.build` "
+                      "(there is no CPU fallback)")
+_lib = C.CDLL(LIB_PATH)
+
+_p, _i, _sz, _f = C.c_void_p, C.c_int, C.c_size_t, C.c_float
+_lib.mate_segments_bytes.restype = _sz
+_lib.mate_segments_bytes.argtypes = [_i, _i]
+_lib.mate_workspace_bytes.restype = _sz
+_lib.mate_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
+_lib.mate_build_segments.restype = _i
+_lib.mate_build_segments.argtypes = [_p, _p, _p, _i, _i, _p, _p]
+_lib.mate_segments_export.restype = _i
+_lib.mate_segments_export.argtypes = [_p, _i, _i, _i, _p, _p, _p, _p, _p, _p]
+_lib.mate_attn_fwd.restype = _i
+_lib.mate_attn_fwd.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _p, _p, _sz, _p]
+_lib.mate_attn_bwd.restype = _i
+_lib.mate_attn_bwd.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
+                               _p, _p, _p, _p, _sz, _p]
+_lib.mate_status_string.restype = C.c_char_p
+_lib.mate_status_string.argtypes = [_i]
+
+mate_segments_bytes = _lib.mate_segments_bytes
+mate_workspace_bytes = _lib.mate_workspace_bytes
+mate_build_segments = _lib.mate_build_segments
+mate_segments_export = _lib.mate_segments_export
+mate_attn_fwd = _lib.mate_attn_fwd
+mate_attn_bwd = _lib.mate_attn_bwd
+
+
+def mate_status_string(status: int) -> str:
+    return _lib.mate_status_string(int(status)).decode()
+
+
+class MateError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {mate_status_string(status)} ({status})")
+        self.status = status
+
+
+def _check(status: int, where: str):
+    if status != MATE_OK:
+        raise MateError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MATE_F32
+    if t.dtype == torch.bfloat16:
+        return MATE_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return t.data_ptr()
+
+
+@dataclass
+class Segments:
+    """Device buffer holding the tables of mate_build_segments for (B, N)."""
+    buf: torch.Tensor
+    B: int
+    N: int
+
+
+def build_segments(row_ids: torch.Tensor, col_ids: torch.Tensor, flags: torch.Tensor,
+                   out: Segments | None = None) -> Segments:
+    B, N = flags.shape
+    assert row_ids.dtype == torch.int32 and col_ids.dtype == torch.int32 and flags.dtype == torch.uint8
+    assert row_ids.shape == (B, N) and col_ids.shape == (B, N)
+    nbytes = mate_segments_bytes(B, N)
+    if nbytes == 0:
+        raise MateError(MATE_ERR_SHAPE, "mate_segments_bytes")
+    if out is None:
+        out = Segments(torch.empty(nbytes, dtype=torch.uint8, device=flags.device), B, N)
+    _check(mate_build_segments(_dev(row_ids, "row_ids"), _dev(col_ids, "col_ids"),
+                               _dev(flags, "flags"), B, N, out.buf.data_ptr(), _stream()),
+           "mate_build_segments")
+    return out
+
+
+def segments_export(seg: Segments, view: int) -> dict:
+    B, N = seg.B, seg.N
+    perm = np.empty((B, N), np.int32)
+    seg_off = np.empty((B, N + 1), np.int32)
+    seg_of_tok = np.empty((B, N), np.int32)
+    global_idx = np.empty((B, N), np.int32)
+    counts = np.empty((B, 3), np.int32)
+    _check(mate_segments_export(seg.buf.data_ptr(), B, N, view, perm.ctypes.data,
+                                seg_off.ctypes.data, seg_of_tok.ctypes.data,
+                                global_idx.ctypes.data, counts.ctypes.data, _stream()),
+           "mate_segments_export")
+    return dict(perm=perm, seg_off=seg_off, seg_of_tok=seg_of_tok, global_idx=global_idx,
+                counts=counts)
+
+
+def _head_kind_host(head_kind, H: int):
+    hk = np.ascontiguousarray(np.asarray(head_kind, dtype=np.uint8))
+    assert hk.shape == (H,)
+    return hk
+
+
+def workspace(B, H, N, D, dtype_code, for_bwd, device) -> torch.Tensor:
+    n = mate_workspace_bytes(B, H, N, D, dtype_code, int(for_bwd))
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def attn_fwd(q, k, v, seg: Segments, head_kind, scale: float, out=None, lse=None, ws=None):
+    B, H, N, D = q.shape
+    hk = _head_kind_host(head_kind, H)
+    code = _dtype_code(q)
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    if ws is None:
+        ws = workspace(B, H, N, D, code, False, q.device)
+    _check(mate_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), seg.buf.data_ptr(),
+                         hk.ctypes.data, B, H, N, D, code, float(scale), _dev(out, "out"),
+                         _dev(lse, "lse"), ws.data_ptr(), ws.numel(), _stream()),
+           "mate_attn_fwd")
+    return out, lse
+
+
+def attn_bwd(q, k, v, out, lse, dout, seg: Segments, head_kind, scale: float,
+             dq=None, dk=None, dv=None, ws=None):
+    B, H, N, D = q.shape
+    hk = _head_kind_host(head_kind, H)
+    code = _dtype_code(q)
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    if ws is None:
+        ws = workspace(B, H, N, D, code, True, q.device)
+    _check(mate_attn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"),
+                         _dev(lse, "lse"), _dev(dout, "dout"), seg.buf.data_ptr(),
+                         hk.ctypes.data, B, H, N, D, code, float(scale), _dev(dq, "dq"),
+                         _dev(dk, "dk"), _dev(dv, "dv"), ws.data_ptr(), ws.numel(), _stream()),
+           "mate_attn_bwd")
+    return dq, dk, dv

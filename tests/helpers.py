@@ -1,0 +1,104 @@
+"""Shared plumbing for the GPU parity tests: moving seeded inputs to the device, calling the
+HIP path through the binding, calling the oracle on the same inputs, and the tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import mate_oracle as orc
+from paper_2109_04312_amd import synth
+
+# Acceptance tolerances (stated with the benchmark definition): fp32 -> 1e-4 max-abs;
+# bf16 in/out with fp32 accumulation -> 2e-2 max-abs and 1e-2 mean-rel, where
+# mean-rel = mean|x - ref| / mean|ref| over the non-pad elements of one tensor.
+# Outputs are rounded to bf16 on store, which alone costs |ref| * 2^-9, so the max-abs bound
+# is applied relative to max(1, |ref|).
+TOL = {"f32": dict(max_abs=1e-4, mean_rel=None), "bf16": dict(max_abs=2e-2, mean_rel=1e-2)}
+
+
+def torch_dtype(name):
+    return torch.float32 if name == "f32" else torch.bfloat16
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x)).to(torch_dtype(dtype)).cuda()
+
+
+def dev_structure(st: synth.Structure):
+    return (torch.from_numpy(st.row_ids).cuda(), torch.from_numpy(st.col_ids).cuda(),
+            torch.from_numpy(st.flags).cuda())
+
+
+def run_hip(w: synth.Workload, backward: bool):
+    """Whole path on the GPU through the C ABI; returns float64 numpy arrays."""
+    from paper_2109_04312_amd import mate
+    r, c, f = dev_structure(w.structure)
+    seg = mate.build_segments(r, c, f)
+    q, k, v = (to_dev(x, w.dtype) for x in (w.q, w.k, w.v))
+    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale)
+    res = dict(o=out, lse=lse)
+    if backward:
+        do = to_dev(w.do, w.dtype)
+        dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale)
+        res.update(dq=dq, dk=dk, dv=dv)
+    torch.cuda.synchronize()
+    return {n: t.float().cpu().numpy().astype(np.float64) for n, t in res.items()}, seg
+
+
+def run_oracle(w: synth.Workload, backward: bool, pairs=None):
+    """Oracle on all (b, h) or on the listed (b, h) pairs; returns {(b,h): dict of [N,..] arrays}."""
+    st = w.structure
+    B, H = w.q.shape[:2]
+    pairs = [(b, h) for b in range(B) for h in range(H)] if pairs is None else pairs
+    res = {}
+    for b, h in pairs:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        args = (st.row_ids[b:b + 1], st.col_ids[b:b + 1], st.flags[b:b + 1], w.head_kind[h:h + 1], w.scale)
+        o, lse = orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args)
+        d = dict(o=o[0, 0], lse=lse[0, 0])
+        if backward:
+            dq, dk, dv = orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args)
+            d.update(dq=dq[0, 0], dk=dk[0, 0], dv=dv[0, 0])
+        res[(b, h)] = d
+    return res
+
+
+def compare(got: dict, ref: dict, w: synth.Workload, label=""):
+    """Element-by-element comparison on every (b,h) the oracle result holds."""
+    tol = TOL[w.dtype]
+    worst = {}
+    for (b, h), d in ref.items():
+        nonpad = w.structure.flags[b] != synth.TOK_PAD
+        for name, r in d.items():
+            g = got[name][b, h]
+            if name != "lse":
+                assert np.all(g[~nonpad] == 0), f"{label} {name}[{b},{h}] non-zero at pad positions"
+            g, r = g[nonpad], r[nonpad]
+            assert np.all(np.isfinite(g)), f"{label} {name}[{b},{h}] not finite"
+            err = np.abs(g - r)
+            rel_max = float((err / np.maximum(1.0, np.abs(r))).max()) if err.size else 0.0
+            # an absolute floor keeps the ratio meaningful where the exact result is ~0
+            # (e.g. dQ of a token that attends only to itself)
+            mean_rel = float(err.mean() / (np.abs(r).mean() + 1e-3)) if err.size else 0.0
+            wkey = worst.setdefault(name, [0.0, 0.0])
+            wkey[0] = max(wkey[0], rel_max)
+            wkey[1] = max(wkey[1], mean_rel)
+            assert rel_max <= tol["max_abs"], f"{label} {name}[{b},{h}] max-abs {rel_max:.3e}"
+            if tol["mean_rel"] is not None and name != "lse":
+                assert mean_rel <= tol["mean_rel"], f"{label} {name}[{b},{h}] mean-rel {mean_rel:.3e}"
+    return worst
+
+
+def compare_segments(seg, st: synth.Structure):
+    """Bit-exact comparison of every exported table with the oracle's."""
+    from paper_2109_04312_amd import mate
+    ref = orc.build_segments(st.row_ids, st.col_ids, st.flags)
+    for view in (0, 1):
+        got = mate.segments_export(seg, view)
+        assert np.array_equal(got["perm"], ref["perm"][view]), f"perm view {view}"
+        assert np.array_equal(got["seg_off"], ref["seg_off"][view]), f"seg_off view {view}"
+        assert np.array_equal(got["seg_of_tok"], ref["seg_of_tok"][view]), f"seg_of_tok view {view}"
+        assert np.array_equal(got["global_idx"], ref["global_idx"]), "global_idx"
+        assert np.array_equal(got["counts"][:, 0], ref["counts"][:, 0])
+        assert np.array_equal(got["counts"][:, 1], ref["counts"][:, 1])
+        assert np.array_equal(got["counts"][:, 2], ref["counts"][:, 2 + view])

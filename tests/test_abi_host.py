@@ -1,0 +1,75 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU (no compute calls here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mate.h")
+
+
+@pytest.fixture(scope="module")
+def mate():
+    from paper_2109_04312_amd import mate as m
+    return m
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(mate_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(mate):
+    names = declared_functions()
+    assert set(names) == set(mate.EXPORTS)
+    lib = C.CDLL(mate.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_size_queries(mate):
+    assert mate.mate_segments_bytes(0, 128) == 0
+    assert mate.mate_segments_bytes(1, 0) == 0
+    assert mate.mate_segments_bytes(1, mate.MATE_MAX_N + 1) == 0
+    small, big = mate.mate_segments_bytes(1, 128), mate.mate_segments_bytes(2, 8192)
+    assert 0 < small < big and big % 4 == 0
+    # ~14 int32 words per token (two views of perm, seg_off, seg_of_tok, slot range + two lists)
+    assert big < 2 * 8192 * 4 * 16
+    assert mate.mate_workspace_bytes(2, 16, 8192, 64, mate.MATE_BF16, 0) >= 0
+    assert mate.mate_workspace_bytes(2, 16, 8192, 64, mate.MATE_BF16, 1) >= 2 * 16 * 8192 * 4
+    assert mate.mate_workspace_bytes(2, 16, 8192, 32, mate.MATE_BF16, 1) == 0
+
+
+def test_status_strings(mate):
+    seen = {mate.mate_status_string(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and "ok" in seen
+    assert mate.mate_status_string(-99) == "unknown status"
+
+
+def test_argument_errors_are_caught_on_the_host(mate):
+    hk = np.zeros(4, np.uint8)
+    fake = 0x1000  # never dereferenced: every call below must fail validation first
+    f = mate.mate_attn_fwd
+    assert f(None, fake, fake, fake, hk.ctypes.data, 1, 4, 128, 64, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_NULL
+    assert f(fake, fake, fake, None, hk.ctypes.data, 1, 4, 128, 64, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_NULL
+    assert f(fake, fake, fake, fake, hk.ctypes.data, 1, 4, 128, 32, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_UNSUPPORTED
+    assert f(fake, fake, fake, fake, hk.ctypes.data, 1, 4, 128, 64, 5, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_UNSUPPORTED
+    assert f(fake, fake, fake, fake, hk.ctypes.data, 0, 4, 128, 64, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_SHAPE
+    assert f(fake, fake, fake, fake, hk.ctypes.data, 1, 4, 1 << 20, 64, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_SHAPE
+    assert f(fake, fake, fake, fake, hk.ctypes.data, 1, 999, 128, 64, 0, 1.0, fake, fake, None, 0, None) == mate.MATE_ERR_SHAPE
+    g = mate.mate_attn_bwd
+    args = [fake] * 7 + [hk.ctypes.data, 1, 4, 128, 64, 1, 1.0, fake, fake, fake]
+    assert g(*args, None, 0, None) == mate.MATE_ERR_WORKSPACE
+    assert g(*args, fake, 16, None) == mate.MATE_ERR_WORKSPACE
+    bad = list(args)
+    bad[14] = None
+    assert g(*bad, fake, 1 << 30, None) == mate.MATE_ERR_NULL
+    b = mate.mate_build_segments
+    assert b(None, fake, fake, 1, 128, fake, None) == mate.MATE_ERR_NULL
+    assert b(fake, fake, fake, 1, 0, fake, None) == mate.MATE_ERR_SHAPE
+    assert mate.mate_segments_export(None, 1, 128, 0, None, None, None, None, None, None) == mate.MATE_ERR_NULL
+    assert mate.mate_segments_export(fake, 1, 128, 2, None, None, None, None, None, None) == mate.MATE_ERR_SHAPE

@@ -1,0 +1,128 @@
+"""GPU parity: forward and backward vs the float64 oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2109_04312_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+ROW, COL = synth.HEAD_ROW, synth.HEAD_COL
+
+
+def small_workload(seed, dtype, B=2, N=200, H=4, bwd=True, **kw):
+    rng = np.random.default_rng(seed)
+    st = synth.random_structure(rng, B, N, **kw)
+    q, k, v, do = synth.draw_tensors(rng, B, H, N, 64, dtype, 4)
+    hk = np.array([ROW, COL] * (H // 2), np.uint8)
+    return synth.Workload(f"small{seed}", dtype, st, hk, q, k, v, do if bwd else None, 0.125)
+
+
+def check_workload(w, backward, pairs=None, label=""):
+    print(f"case {label or w.name} dtype={w.dtype} shape={w.shape} bwd={backward}", flush=True)
+    got, seg = hp.run_hip(w, backward)
+    hp.compare_segments(seg, w.structure)
+    ref = hp.run_oracle(w, backward, pairs)
+    worst = hp.compare(got, ref, w, label or w.name)
+    print("   worst (max-abs rel. to max(1,|ref|), mean-rel):",
+          {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in worst.items()}, flush=True)
+
+
+def test_config1_tiny_f32_forward():
+    check_workload(synth.make_config(1), backward=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_small_scattered_fwd_bwd(seed, dtype):
+    w = small_workload(seed, dtype, N=[200, 333, 130][seed], max_rows=12, max_cols=7, max_global=20,
+                       max_cell=4, scatter=seed != 0, sparse_ids=seed == 2)
+    check_workload(w, backward=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_structures(dtype):
+    """All pad, all global (dense), no globals, one row, one column, single tokens."""
+    L, G, P = synth.TOK_LOCAL, synth.TOK_GLOBAL, synth.TOK_PAD
+    N = 150
+    rng = np.random.default_rng(12)
+    flags = np.full((7, N), L, np.uint8)
+    row = rng.integers(0, 9, (7, N)).astype(np.int32)
+    col = rng.integers(0, 4, (7, N)).astype(np.int32)
+    flags[0] = P                                   # empty sequence
+    flags[1] = G                                   # dense attention
+    flags[1, 100:] = P
+    row[3] = 5                                     # one row, no globals  (flags[2]: generic, no globals)
+    col[4] = 1                                     # one column
+    flags[4, :3] = G
+    flags[5] = P                                   # a single table token
+    flags[5, 77] = L
+    flags[6] = P                                   # one global + one local
+    flags[6, 3] = G
+    flags[6, 140] = L
+    st = synth.Structure(row, col, flags)
+    q, k, v, do = synth.draw_tensors(rng, 7, 2, N, 64, dtype, 4)
+    w = synth.Workload("degenerate", dtype, st, np.array([ROW, COL], np.uint8), q, k, v, do, 0.125)
+    check_workload(w, backward=True)
+
+
+def test_config2_bf16_fwd_bwd():
+    check_workload(synth.make_config(2), backward=True)
+
+
+def test_config3_bf16_fwd_bwd():
+    w = synth.make_config(3)
+    pairs = [(b, h) for b in (0, 5) for h in (0, 7, 8, 15)]
+    check_workload(w, backward=True, pairs=pairs)
+
+
+def test_config4_headline_sampled_heads():
+    # Full benchmark size, the launch configuration bench.py times; the oracle evaluates a
+    # sample of (sequence, head) pairs completely (a row head and a column head per sequence).
+    w = synth.make_config(4)
+    check_workload(w, backward=True, pairs=[(0, 0), (0, 15), (1, 7), (1, 8)])
+
+
+def test_config5_ragged_sampled_heads():
+    w = synth.make_config(5)
+    # b=0: one-row table (row heads dense), b=1: one-column table (column heads dense)
+    check_workload(w, backward=True, pairs=[(0, 0), (0, 8), (1, 3), (1, 12), (9, 1), (15, 14)])
+
+
+def test_backward_is_bit_reproducible():
+    from paper_2109_04312_amd import mate
+    w = small_workload(5, "bf16", B=2, N=700, H=4, max_rows=40, max_cols=6, max_global=70, max_cell=5)
+    r, c, f = hp.dev_structure(w.structure)
+    seg = mate.build_segments(r, c, f)
+    q, k, v, do = (hp.to_dev(x, "bf16") for x in (w.q, w.k, w.v, w.do))
+    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale)
+    a = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale)
+    b = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale)
+    out2, lse2 = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+
+
+def test_head_kind_mix_and_order():
+    # any assignment of kinds to heads, not only "first half rows"
+    w = small_workload(8, "bf16", B=1, N=260, H=5, max_rows=10, max_cols=5, max_global=9)
+    w.head_kind = np.array([COL, COL, ROW, COL, ROW], np.uint8)
+    check_workload(w, backward=True)
+
+
+def test_argument_errors_leave_outputs_untouched():
+    from paper_2109_04312_amd import mate
+    w = small_workload(1, "f32", B=1, N=64, H=2, bwd=False)
+    r, c, f = hp.dev_structure(w.structure)
+    seg = mate.build_segments(r, c, f)
+    q = hp.to_dev(w.q, "f32")
+    out = torch.full_like(q, 7.0)
+    lse = torch.full((1, 2, 64), 7.0, device="cuda")
+    hk = np.array([0, 9], np.uint8)
+    st = mate.mate_attn_fwd(q.data_ptr(), q.data_ptr(), q.data_ptr(), seg.buf.data_ptr(), hk.ctypes.data,
+                            1, 2, 64, 64, 0, 0.125, out.data_ptr(), lse.data_ptr(), None, 0, None)
+    assert st == mate.MATE_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((out == 7).all()) and bool((lse == 7).all())

@@ -1,0 +1,82 @@
+"""GPU parity: segment builder vs the oracle's stable sort, bit-exact, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2109_04312_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(st):
+    from paper_2109_04312_amd import mate
+    r, c, f = hp.dev_structure(st)
+    return mate.build_segments(r, c, f)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_segments_benchmark_configs(idx):
+    print(f"segments config {idx}", flush=True)
+    w = synth.make_config(idx, tensors=False)
+    hp.compare_segments(_build(w.structure), w.structure)
+
+
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 1000, 1024, 1025, 4097, 8192, 9000, 16384])
+def test_segments_sizes_scattered_sparse_ids(N):
+    print(f"segments N={N}", flush=True)
+    rng = np.random.default_rng(N)
+    st = synth.random_structure(rng, 3, N, max_rows=max(1, min(300, N // 3)), max_cols=12,
+                                max_global=min(N, 40), max_cell=4, scatter=True, sparse_ids=True)
+    hp.compare_segments(_build(st), st)
+
+
+def test_segments_degenerate_sequences():
+    N = 300
+    L, G, P = synth.TOK_LOCAL, synth.TOK_GLOBAL, synth.TOK_PAD
+    flags = np.stack([np.full(N, P), np.full(N, G), np.full(N, L), np.full(N, L), np.full(N, L)]).astype(np.uint8)
+    row = np.zeros((5, N), np.int32)
+    col = np.zeros((5, N), np.int32)
+    row[3] = np.arange(N)[::-1]              # every token its own row, descending ids
+    col[3] = 2**31 - 1                       # one column with the largest id
+    row[4] = np.arange(N) % 7
+    col[4] = (np.arange(N) * 2654435761 % 2**31).astype(np.int64) % 5
+    st = synth.Structure(row, col, flags)
+    hp.compare_segments(_build(st), st)
+
+
+def test_segments_bad_ids_reported():
+    from paper_2109_04312_amd import mate
+    N = 70
+    flags = np.zeros((2, N), np.uint8)
+    row = np.ones((2, N), np.int32)
+    col = np.ones((2, N), np.int32)
+    st = synth.Structure(row, col, flags)
+    seg = _build(st)
+    mate.segments_export(seg, 0)             # clean input: no error
+    row2 = row.copy()
+    row2[1, 5] = -3
+    with pytest.raises(mate.MateError) as e:
+        mate.segments_export(_build(synth.Structure(row2, col, flags)), 0)
+    assert e.value.status == mate.MATE_ERR_BAD_ID
+    flags2 = flags.copy()
+    flags2[0, 9] = 7
+    with pytest.raises(mate.MateError) as e:
+        mate.segments_export(_build(synth.Structure(row, col, flags2)), 1)
+    assert e.value.status == mate.MATE_ERR_BAD_ID
+
+
+def test_segments_rebuild_is_deterministic_and_reusable():
+    from paper_2109_04312_amd import mate
+    rng = np.random.default_rng(3)
+    st1 = synth.random_structure(rng, 4, 777, max_rows=50, max_cols=9, scatter=True)
+    st2 = synth.random_structure(rng, 4, 777, max_rows=20, max_cols=3)
+    seg = _build(st1)
+    a = seg.buf.clone()
+    r, c, f = hp.dev_structure(st2)
+    mate.build_segments(r, c, f, out=seg)     # overwrite in place with another batch
+    hp.compare_segments(seg, st2)
+    r, c, f = hp.dev_structure(st1)
+    mate.build_segments(r, c, f, out=seg)
+    torch.cuda.synchronize()
+    assert torch.equal(seg.buf, a)
