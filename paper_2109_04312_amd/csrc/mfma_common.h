@@ -1,0 +1,106 @@
+// Device helpers shared by the bf16 MFMA attention kernels (gfx950, wave64).
+//
+// MFMA used: v_mfma_f32_32x32x16_bf16.  Operand layout, lane l = 32*hl + m (m = l % 32):
+//   A (32 x 16): lane holds row m,    k = 8*hl .. 8*hl+7   (8 bf16 = 16 bytes)
+//   B (16 x 32): lane holds column m, k = 8*hl .. 8*hl+7
+//   C (32 x 32): lane holds column m, register c = 4*g + r  <->  row 8*g + 4*hl + r
+// Every kernel here computes "transposed" score tiles (rows = keys or queries of the streamed
+// tile, columns = the rows the wavefront owns), so each lane owns one of the wavefront's rows
+// and per-row softmax statistics are per-lane scalars.
+//
+// Row permutation rho.  The 32 rows of a streamed tile are fed to the A operand permuted
+// (A row m' is tile row rho(m'), rho swaps bits 2 and 3), so that the eight C registers
+// c = 8*t .. 8*t+7 of a lane are the eight CONSECUTIVE tile rows 16*t + 8*hl + 0..7 -- which is
+// exactly the k-slice a lane must supply when those registers are fed back as the B operand of
+// the second contraction.  tile_row(c, hl) below is that map.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace mate {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kD = 64;             // head size
+constexpr int kLdsRow = kD + 8;    // LDS row pitch in bf16 elements (144 bytes: 16-byte aligned,
+                                   // and consecutive rows start 4 banks apart)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ inline int rho(int m) {  // swap bits 2 and 3 of a 5-bit row index
+  return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1);
+}
+// Tile row (0..31) held in C register c (0..15) of a lane in half hl.
+__device__ inline int tile_row(int c, int hl) { return 16 * (c >> 3) + 8 * hl + (c & 7); }
+
+__device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// Registers c0 .. c0+7 of a C tile, rounded to bf16 (nearest even), as an MFMA operand.
+__device__ inline bf16x8 pack8(const f32x16& x, int c0) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[c0 + e];
+  return r;
+}
+
+__device__ inline bf16x8 lds_read8(const unsigned short* p) {
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8 b; } x;
+  x.u = v;
+  return x.b;
+}
+
+__device__ inline unsigned short f32_to_bf16_bits(float x) {
+  __bf16 h = (__bf16)x;
+  return __builtin_bit_cast(unsigned short, h);
+}
+
+// Four keys' rows (8 head dims each, r[j] = dims d0..d0+7 of key j) -> for each dim the four
+// keys packed as 8 bytes: the transposing step when a streamed tile is written to LDS as
+// [dim][key].
+__device__ inline uint2 transpose_pick(const uint4 r[4], int e) {
+  const unsigned w0 = (&r[0].x)[e >> 1], w1 = (&r[1].x)[e >> 1];
+  const unsigned w2 = (&r[2].x)[e >> 1], w3 = (&r[3].x)[e >> 1];
+  uint2 o;
+  if (e & 1) {
+    o.x = (w0 >> 16) | (w1 & 0xffff0000u);
+    o.y = (w2 >> 16) | (w3 & 0xffff0000u);
+  } else {
+    o.x = (w0 & 0xffffu) | (w1 << 16);
+    o.y = (w2 & 0xffffu) | (w3 << 16);
+  }
+  return o;
+}
+
+// Work distribution.  Consecutive workgroup ids land on different XCDs (8 of them, each with
+// its own L2).  All tiles of one (sequence, head) are given ids congruent mod 8 so they share
+// an L2; tile 0 of every (b, h) comes first, then tile 1, ... so long tiles start early.
+struct TileId {
+  int bh, tile;
+  bool valid;
+};
+__device__ inline TileId map_block(int bid, int BH) {
+  const int groups = (BH + 7) >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
+  TileId t;
+  t.bh = (slot % groups) * 8 + xcd;
+  t.tile = slot / groups;
+  t.valid = t.bh < BH;
+  return t;
+}
+inline int grid_blocks(int BH, int tiles) { return ((BH + 7) >> 3) * 8 * tiles; }
+
+}  // namespace mate
