@@ -42,7 +42,7 @@ typedef enum {
   MATE_OK = 0,
   MATE_ERR_NULL = -1,        /* a required pointer is NULL                                */
   MATE_ERR_SHAPE = -2,       /* B, H, N out of range, or tables built for another (B, N)  */
-  MATE_ERR_UNSUPPORTED = -3, /* D != 64, unknown dtype, unknown head kind                 */
+  MATE_ERR_UNSUPPORTED = -3, /* D != 64, unknown dtype or head kind, scale not positive   */
   MATE_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than mate_workspace_bytes(...)    */
   MATE_ERR_BAD_ID = -5,      /* a table token has a negative id, or a flag value > 2      */
   MATE_ERR_HIP = -6          /* a HIP call or kernel launch failed                        */
@@ -116,7 +116,8 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
  *               rounded to bf16 before multiplying V; f32: fp32 throughout)
  *   segments    tables from mate_build_segments for the same (B, N)
  *   head_kind   HOST [H] uint8, MATE_HEAD_*
- *   scale       softmax scale (the appendix listing uses 1/sqrt(D))
+ *   scale       softmax scale, positive and finite (the appendix listing uses 1/sqrt(D));
+ *               anything else is MATE_ERR_UNSUPPORTED
  *   out         [B, H, N, D] dtype t;  lse [B, H, N] float
  *   workspace   mate_workspace_bytes(..., 0) bytes (may be NULL if that is 0)
  *

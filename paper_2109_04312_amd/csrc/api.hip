@@ -8,6 +8,7 @@
 #include "../../include/mate.h"
 #include "launch.h"
 #include "seg_layout.h"
+#include "stream_plan.h"
 
 using namespace mate;
 
@@ -15,13 +16,18 @@ namespace {
 
 bool shape_ok(int B, int N) { return B >= 1 && N >= 1 && N <= MATE_MAX_N; }
 
-size_t delta_bytes(int B, int H, int N) { return (size_t)B * H * N * sizeof(float); }
+size_t align16(size_t n) { return (n + 15) & ~size_t(15); }
+size_t delta_bytes(int B, int H, int N) { return align16((size_t)B * H * N * sizeof(float)); }
+// partial results of chunked question-token owners (bf16 MFMA path only)
+size_t part_bytes(int B, int H, int N) { return (size_t)B * H * part_words_per_bh(N) * sizeof(float); }
+size_t stat_bytes(int B, int H, int N) { return (size_t)B * H * stat_words_per_bh(N) * sizeof(float); }
 
 mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kind, int B, int H,
                       int N, int D, mate_dtype t, float scale) {
   if (!segments || !head_kind) return MATE_ERR_NULL;
   if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS) return MATE_ERR_SHAPE;
   if (D != MATE_HEAD_DIM || (t != MATE_F32 && t != MATE_BF16)) return MATE_ERR_UNSUPPORTED;
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) return MATE_ERR_UNSUPPORTED;
   std::memset(&a, 0, sizeof(a));
   for (int h = 0; h < H; ++h) {
     if (head_kind[h] > MATE_HEAD_COL) return MATE_ERR_UNSUPPORTED;
@@ -45,9 +51,11 @@ size_t mate_segments_bytes(int B, int N) {
 }
 
 size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bwd) {
-  (void)t;
   if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS || D != MATE_HEAD_DIM) return 0;
-  return for_bwd ? delta_bytes(B, H, N) : 0;
+  if (t == MATE_F32) return for_bwd ? delta_bytes(B, H, N) : 0;
+  if (t != MATE_BF16) return 0;
+  return for_bwd ? delta_bytes(B, H, N) + 3 * part_bytes(B, H, N)
+                 : part_bytes(B, H, N) + stat_bytes(B, H, N);
 }
 
 mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
@@ -107,6 +115,10 @@ mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const voi
   const size_t need = mate_workspace_bytes(B, H, N, D, t, 0);
   if (need && (!workspace || workspace_bytes < need)) return MATE_ERR_WORKSPACE;
   a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse;
+  if (t == MATE_BF16) {
+    a.part[0] = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_bytes(B, H, N));
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = (t == MATE_BF16) ? launch_fwd_mfma(a, s) : launch_fwd_scalar(a, false, s);
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
@@ -127,6 +139,10 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
   a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.delta = static_cast<float*>(workspace);
+  if (t == MATE_BF16) {
+    char* p = static_cast<char*>(workspace) + delta_bytes(B, H, N);
+    for (int i = 0; i < 3; ++i) a.part[i] = reinterpret_cast<float*>(p + i * part_bytes(B, H, N));
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = (t == MATE_BF16) ? launch_bwd_mfma(a, s) : launch_bwd_scalar(a, false, s);
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;

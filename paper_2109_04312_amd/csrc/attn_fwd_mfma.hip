@@ -5,83 +5,35 @@
 // kind's sorted order -- or 128 question tokens, or 128 pad tokens (zero fill).  It streams the
 // keys those queries may see in 64-key tiles: first the question tokens (gathered through
 // global_idx), then the sorted slots spanned by the queries' own row / column segments
-// (gathered through perm; every table token for a question-token tile).  Each key tile is
-// staged in LDS once (K as [key][dim], V transposed to [dim][key]) and used by all four
-// wavefronts; scores are masked per element by "key slot inside this query's segment range",
-// and one online softmax runs across the question-key and segment-key tiles, which is the
-// single softmax over the union that the definition asks for.
+// (gathered through perm; every table token for question-token owners, whose key stream is cut
+// into chunks run by separate workgroups).  Each key tile is staged in LDS once (K as
+// [key][dim], V transposed to [dim][key]) and used by all four wavefronts; scores are masked per
+// element by "key slot inside this query's segment range", and one online softmax runs across
+// the question-key and segment-key tiles, which is the single softmax over the union that the
+// definition asks for.  Chunked owners leave (unnormalised O, max, sum) partials that the
+// finalize kernel merges with the usual log-sum-exp rule.
 #include <hip/hip_runtime.h>
 
 #include "launch.h"
 #include "mfma_common.h"
+#include "stream_plan.h"
 
 namespace mate {
 namespace {
-
-constexpr int BM = 128;  // queries per workgroup (32 per wavefront)
-constexpr int BN = 64;   // keys per streamed tile
-constexpr int kThreads = 256;
-constexpr int kTileElems = BN * kLdsRow;  // one staged K (or V^T) tile, in bf16 elements
-
-struct KeyTileRegs {
-  uint4 r[4];
-};
-
-// Thread roles when staging a key tile: wavefronts 0-1 copy K rows (4 x 16 bytes each),
-// wavefronts 2-3 take V, four keys x eight dims per thread, and write it transposed.
-__device__ inline void load_key_tile(KeyTileRegs& t, const unsigned short* __restrict__ K,
-                                     const unsigned short* __restrict__ V,
-                                     const int* __restrict__ list, int base, int last, int tid) {
-  if (tid < 128) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int piece = tid + 128 * u;  // 512 pieces of 16 bytes
-      const int row = piece >> 3, col = piece & 7;
-      const int tok = list[min(base + row, last)];
-      t.r[u] = *reinterpret_cast<const uint4*>(K + (size_t)tok * kD + col * 8);
-    }
-  } else {
-    const int x = tid - 128, jg = x & 15, dg = x >> 4;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int tok = list[min(base + jg * 4 + u, last)];
-      t.r[u] = *reinterpret_cast<const uint4*>(V + (size_t)tok * kD + dg * 8);
-    }
-  }
-}
-
-__device__ inline void store_key_tile(const KeyTileRegs& t, unsigned short* Ks, unsigned short* Vt,
-                                      int tid) {
-  if (tid < 128) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int piece = tid + 128 * u;
-      const int row = piece >> 3, col = piece & 7;
-      *reinterpret_cast<uint4*>(Ks + row * kLdsRow + col * 8) = t.r[u];
-    }
-  } else {
-    const int x = tid - 128, jg = x & 15, dg = x >> 4;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      *reinterpret_cast<uint2*>(Vt + (dg * 8 + e) * kLdsRow + jg * 4) = transpose_pick(t.r, e);
-  }
-}
 
 __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned short lds[4 * kTileElems];  // 2 x (K, V^T)
   __shared__ int q_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid) return;
+  if (!id.valid || !tables_match(a)) return;
   const int b = id.bh / a.H, h = id.bh % a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
-  if (a.seg.hdr[0] != kMagic || a.seg.hdr[1] != a.B || a.seg.hdr[2] != N) return;
+  const UnitPlan u = plan_unit(a, b, view, id.tile);
+  if (u.kind == UNIT_NONE) return;
 
-  const int* cnt = a.seg.counts + (size_t)b * kCountWords;
-  const int G = cnt[C_G], L = cnt[C_L], P = cnt[C_P];
-  const int n_gt = (G + BM - 1) / BM, n_lt = (L + BM - 1) / BM, n_pt = (P + BM - 1) / BM;
   const size_t bh = (size_t)id.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
   const unsigned short* K = static_cast<const unsigned short*>(a.k) + bh * kD;
@@ -90,99 +42,60 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
   float* LSE = a.lse + bh;
   const int* global_idx = a.seg.global_idx + (size_t)b * N;
 
-  int tile = id.tile;
-  if (tile >= n_gt + n_lt + n_pt) return;
-  if (tile >= n_gt + n_lt) {  // pad positions: O = 0, LSE = 0
-    const int t0 = (tile - n_gt - n_lt) * BM;
-    const int* pad_idx = a.seg.pad_idx + (size_t)b * N;
-    for (int x = tid; x < BM * 8; x += kThreads) {
-      const int row = x >> 3, piece = x & 7;
-      if (t0 + row < P) {
-        const int tok = pad_idx[t0 + row];
-        *reinterpret_cast<uint4*>(O + (size_t)tok * kD + piece * 8) = make_uint4(0, 0, 0, 0);
-        if (piece == 0) LSE[tok] = 0.f;
-      }
-    }
+  if (u.kind == UNIT_PAD) {  // pad positions: O = 0, LSE = 0
+    zero_pad_rows(O, u, tid);
+    if (tid < BM && u.t0 + tid < u.own_count) LSE[u.own_list[u.t0 + tid]] = 0.f;
     return;
   }
 
-  // ---- which queries, which keys -------------------------------------------------------
-  const bool is_global = tile < n_gt;
-  const int* q_list;
-  const int* k_list;
-  int t0, q_count, k_lo, k_hi;
-  if (is_global) {
-    t0 = tile * BM;
-    q_list = global_idx;
-    q_count = G;
-    k_list = a.seg.perm[0] + (size_t)b * N;  // all table tokens; row order is the contiguous one
-    k_lo = 0;
-    k_hi = L;
-  } else {
-    t0 = (tile - n_gt) * BM;
-    q_list = a.seg.perm[view] + (size_t)b * N;
-    q_count = L;
-    k_list = q_list;
-    const int2* rng = a.seg.slot_rng[view] + (size_t)b * N;
-    k_lo = rng[t0].x;
-    k_hi = rng[min(t0 + BM, L) - 1].y;
-  }
-  // This lane's query: row m of the wavefront's 32.  Rows past the end repeat the last query
-  // (computed, never stored) so that every lane always has at least one visible key.
-  const int q_slot = min(t0 + wave * 32 + m, q_count - 1);
-  const int q_pos = q_list[q_slot];
-  int my_lo = 0, my_hi = L;
-  if (!is_global) {
-    const int2 r = a.seg.slot_rng[view][(size_t)b * N + q_slot];
-    my_lo = r.x;
-    my_hi = r.y;
-  }
-  // Slot range any query of this wavefront can see (queries are sorted, ranges are monotone).
-  const int w_lo = __shfl(my_lo, 0, 64), w_hi = __shfl(my_hi, 31, 64);
-  // Slot range every query of this wavefront sees (no per-element mask needed inside it).
-  const int w_lo_all = __shfl(my_lo, 31, 64), w_hi_all = __shfl(my_hi, 0, 64);
-  if (tid < BM) q_tok[tid] = t0 + tid < q_count ? q_list[t0 + tid] : -1;
+  const OwnedRow me = owned_row(u, a, b, view, wave, m);
+  if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
 
   bf16x8 qf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
-    qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(Q + (size_t)q_pos * kD + ks * 16 + hl * 8));
+    qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(Q + (size_t)me.pos * kD + ks * 16 + hl * 8));
 
-  const int n_t0 = (G + BN - 1) / BN;                      // question-key tiles
-  const int n_t1 = k_hi > k_lo ? (k_hi - k_lo + BN - 1) / BN : 0;  // segment-key tiles
-  const int n_tiles = n_t0 + n_t1;
-  const float sc = a.scale * kLog2e;
-
+  const float sc = a.scale * kLog2e;  // scores are kept raw; exp2(s * sc - m * sc)
   f32x16 o_acc[2] = {zero16(), zero16()};
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
-  auto tile_src = [&](int t, const int*& list, int& base, int& last) {
-    if (t < n_t0) { list = global_idx; base = t * BN; last = G - 1; }
-    else { list = k_list; base = k_lo + (t - n_t0) * BN; last = k_hi - 1; }
+  // wavefronts 0-1 stage K rows, wavefronts 2-3 stage V transposed.  Token indices are fetched
+  // two tiles ahead and rows one tile ahead, so neither latency sits on the critical path.
+  const unsigned short* stage_src = tid < 128 ? K : V;
+  const int sx = tid & 127;
+  auto fetch_idx = [&](TileIdx& ix, int t) {
+    const int* list; int base, last;
+    tile_source(u, global_idx, t, list, base, last);
+    load_tile_idx(ix, list, base, last, sx);
+  };
+  auto store = [&](const TileRegs& r, int buf) {
+    unsigned short* Ks = lds + buf * 2 * kTileElems;
+    if (tid < 128) store_block4x8(r, Ks, nullptr, tid);
+    else store_block4x8(r, nullptr, Ks + kTileElems, tid - 128);
   };
 
-  KeyTileRegs regs;
-  {
-    const int* list; int base, last;
-    tile_src(0, list, base, last);
-    load_key_tile(regs, K, V, list, base, last, tid);
-    store_key_tile(regs, lds, lds + kTileElems, tid);
-  }
+  TileIdx idx;
+  TileRegs regs;
+  fetch_idx(idx, u.t_begin);
+  load_tile_rows(regs, stage_src, idx, sx);
+  if (u.t_begin + 1 < u.t_end) fetch_idx(idx, u.t_begin + 1);
+  store(regs, 0);
   __syncthreads();
 
-  for (int t = 0; t < n_tiles; ++t) {
-    unsigned short* Ks = lds + (t & 1) * 2 * kTileElems;
-    unsigned short* Vt = Ks + kTileElems;
-    if (t + 1 < n_tiles) {
-      const int* list; int base, last;
-      tile_src(t + 1, list, base, last);
-      load_key_tile(regs, K, V, list, base, last, tid);
+  const int k_off = rho(m) * kLdsRow + hl * 8, v_off = m * kLdsRow + hl * 8;
+  for (int t = u.t_begin; t < u.t_end; ++t) {
+    const int buf = (t - u.t_begin) & 1;
+    const unsigned short* Kp = lds + buf * 2 * kTileElems + k_off;
+    const unsigned short* Vp = lds + buf * 2 * kTileElems + kTileElems + v_off;
+    if (t + 1 < u.t_end) {
+      load_tile_rows(regs, stage_src, idx, sx);
+      if (t + 2 < u.t_end) fetch_idx(idx, t + 2);
     }
     // visible slot window for this tile: question keys [0,G), else this lane's segment range
-    const bool part0 = t < n_t0;
-    const int base = part0 ? t * BN : k_lo + (t - n_t0) * BN;
-    const int lo = part0 ? 0 : my_lo, hi = part0 ? G : my_hi;
-    const bool skip = !part0 && (base >= w_hi || base + BN <= w_lo);
+    const bool part0 = t < u.n_t0;
+    const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
+    const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       // S^T = K Q^T : rows = keys of the tile (permuted by rho), columns = this wave's queries
       f32x16 s[2] = {zero16(), zero16()};
@@ -190,93 +103,119 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-          s[jb] = mfma(lds_read8(Ks + (jb * 32 + rho(m)) * kLdsRow + ks * 16 + hl * 8), qf[ks], s[jb]);
+          s[jb] = mfma(lds_read8(Kp + jb * 32 * kLdsRow + ks * 16), qf[ks], s[jb]);
 
-      const bool full = part0 ? (base + BN <= G) : (base >= w_lo_all && base + BN <= w_hi_all);
-      float mx = -INFINITY;
+      const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
+      if (!full) {  // wave-uniform: some (query, key) pairs of this tile are outside the pattern
+        const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
+        const int d0 = base + 8 * hl - lo;
+        const unsigned len = (unsigned)(hi - lo);
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+        for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          float v = s[jb][c] * sc;
-          if (!full) {
-            const int slot = base + jb * 32 + tile_row(c, hl);
-            if (slot < lo || slot >= hi) v = -INFINITY;
+          for (int c = 0; c < 16; ++c) {
+            const bool in = (unsigned)(d0 + jb * 32 + 16 * (c >> 3) + (c & 7)) < len;
+            s[jb][c] = in ? s[jb][c] : -INFINITY;
           }
-          s[jb][c] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);       // finite from the first visible key on
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      float psum = 0.f;
+      }
+      float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+      for (int c = 1; c < 16; ++c) mx = fmaxf(mx, fmaxf(s[0][c], s[1][c]));
+      mx = half_max(mx);
+      if (__any(mx > m_run)) {  // rescale only when some row's maximum moved
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+        l_run *= alpha;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          const float p = __builtin_amdgcn_exp2f(s[jb][c] - m_use);
-          s[jb][c] = p;
-          psum += p;
-        }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
+        for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+          for (int c = 0; c < 16; ++c) o_acc[db][c] *= alpha;
+        m_run = m_new;
+      }
+      const float msc = m_run == -INFINITY ? 0.f : m_run * sc;
+      // P^T = exp2(S^T sc - m sc), rounded to bf16;  O^T += V^T P^T;  l += sum of rounded P
 #pragma unroll
-        for (int c = 0; c < 16; ++c) o_acc[db][c] *= alpha;
-      // O^T += V^T P^T
+      for (int jb = 0; jb < 2; ++jb) {
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+        for (int c = 0; c < 16; ++c) s[jb][c] = __builtin_amdgcn_exp2f(fmaf(s[jb][c], sc, -msc));
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const bf16x8 pb = pack8(s[jb], 8 * tt);
+          l_run = sum8(pb, l_run);
 #pragma unroll
           for (int db = 0; db < 2; ++db)
-            o_acc[db] = mfma(lds_read8(Vt + (db * 32 + m) * kLdsRow + jb * 32 + tt * 16 + hl * 8),
-                             pb, o_acc[db]);
+            o_acc[db] = mfma(lds_read8(Vp + db * 32 * kLdsRow + jb * 32 + tt * 16), pb, o_acc[db]);
         }
+      }
     }
-    if (t + 1 < n_tiles) {
-      unsigned short* Kn = lds + ((t + 1) & 1) * 2 * kTileElems;
-      store_key_tile(regs, Kn, Kn + kTileElems, tid);
-    }
+    if (t + 1 < u.t_end) store(regs, buf ^ 1);
     __syncthreads();
   }
 
-  // ---- epilogue: normalise, transpose through LDS, store rows of O in token order -------
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = 1.f / l_tot;
-  unsigned short* Os = lds;  // [BM][kLdsRow]; the loop ended on a barrier
-#pragma unroll
-  for (int db = 0; db < 2; ++db)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint2 w;
-      w.x = f32_to_bf16_bits(o_acc[db][4 * g] * inv) |
-            ((unsigned)f32_to_bf16_bits(o_acc[db][4 * g + 1] * inv) << 16);
-      w.y = f32_to_bf16_bits(o_acc[db][4 * g + 2] * inv) |
-            ((unsigned)f32_to_bf16_bits(o_acc[db][4 * g + 3] * inv) << 16);
-      *reinterpret_cast<uint2*>(Os + (wave * 32 + m) * kLdsRow + db * 32 + 8 * g + 4 * hl) = w;
-    }
-  if (hl == 0 && t0 + wave * 32 + m < q_count) LSE[q_pos] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = wave * 32 + it * 8 + (lane >> 3), piece = lane & 7;
-    const int tok = q_tok[row];
-    if (tok >= 0)
-      *reinterpret_cast<uint4*>(O + (size_t)tok * kD + piece * 8) =
-          *reinterpret_cast<const uint4*>(Os + row * kLdsRow + piece * 8);
+  const float l_tot = half_sum(l_run);
+  if (u.part >= 0) {
+    // chunk of a question-token owner: leave (unnormalised O, max, sum) for the finalize kernel
+    const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
+    store_partial(o_acc, 1.f, a.part[0] + slot * BM * kD, wave, lane);
+    if (hl == 0)
+      *reinterpret_cast<float2*>(a.part_ml + (slot * BM + wave * 32 + m) * 2) =
+          make_float2(m_run == -INFINITY ? m_run : m_run * sc, l_tot);
+    return;
+  }
+  if (hl == 0 && me.valid) LSE[me.pos] = (m_run * sc + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  store_owned_rows(o_acc, 1.f / l_tot, lds, O, q_tok, wave, lane);
+}
+
+// Merges the chunk partials of question-token queries: O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
+// 8 threads per query row (8 dims each), 32 rows per workgroup.
+__global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
+  const int bh_i = blockIdx.y, b = bh_i / a.H, N = a.N;
+  if (!tables_match(a)) return;
+  const int* cnt = a.seg.counts + (size_t)b * kCountWords;
+  const int G = cnt[C_G], L = cnt[C_L];
+  const GlobalSplit s = global_split(G, L, N);
+  if (s.n_chunks <= 1) return;
+  const int piece = threadIdx.x & 7;
+  for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
+  const int gt = x / BM, r = x % BM;
+  const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
+  float m = -INFINITY;
+  for (int c = 0; c < s.n_chunks; ++c) m = fmaxf(m, a.part_ml[((slot0 + c) * BM + r) * 2]);
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, l = 0.f;
+  for (int c = 0; c < s.n_chunks; ++c) {
+    const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
+    const float w = __builtin_amdgcn_exp2f(ml.x - m);
+    l += w * ml.y;
+    const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
+    const float4 p0 = *reinterpret_cast<const float4*>(p), p1 = *reinterpret_cast<const float4*>(p + 4);
+    acc[0] += w * p0.x; acc[1] += w * p0.y; acc[2] += w * p0.z; acc[3] += w * p0.w;
+    acc[4] += w * p1.x; acc[5] += w * p1.y; acc[6] += w * p1.z; acc[7] += w * p1.w;
+  }
+  const float inv = 1.f / l;
+  const int tok = a.seg.global_idx[(size_t)b * N + x];
+  const size_t bh = (size_t)bh_i * N;
+  uint4 w;
+  w.x = f32_to_bf16_bits(acc[0] * inv) | ((unsigned)f32_to_bf16_bits(acc[1] * inv) << 16);
+  w.y = f32_to_bf16_bits(acc[2] * inv) | ((unsigned)f32_to_bf16_bits(acc[3] * inv) << 16);
+  w.z = f32_to_bf16_bits(acc[4] * inv) | ((unsigned)f32_to_bf16_bits(acc[5] * inv) << 16);
+  w.w = f32_to_bf16_bits(acc[6] * inv) | ((unsigned)f32_to_bf16_bits(acc[7] * inv) << 16);
+  *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + (bh + tok) * kD + piece * 8) = w;
+  if (piece == 0) a.lse[bh + tok] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
 }
 
 }  // namespace
 
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  const int tiles = (a.N + BM - 1) / BM + 2;  // question + table + pad tiles, each rounded up
-  hipLaunchKernelGGL(fwd_mfma_kernel, dim3(grid_blocks(a.B * a.H, tiles)), dim3(kThreads), 0,
-                     stream, a);
+  hipLaunchKernelGGL(fwd_mfma_kernel, dim3(grid_blocks(a.B * a.H, units_per_bh(a.N))),
+                     dim3(kThreads), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // partials exist only while question tokens fill at most half the owner slots; a few
+  // workgroups per (b,h) stride over however many question tokens there are
+  if (owner_slots(a.N) >= 2)
+    hipLaunchKernelGGL(fwd_finalize_kernel, dim3(kFinalizeBlocks, a.B * a.H), dim3(kThreads), 0,
+                       stream, a);
   return hipGetLastError();
 }
 

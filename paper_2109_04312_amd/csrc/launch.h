@@ -13,6 +13,9 @@ struct AttnArgs {
   float* lse;               // forward: written; backward: read (const in spirit)
   void *dq, *dk, *dv;       // backward only
   float* delta;             // backward scratch [B,H,N]
+  float* part[3];           // partial results of chunked question-token owners, per (b,h):
+                            //   forward: [0] unnormalised O;  backward: dQ, dK, dV
+  float* part_ml;           // forward: running max (log2 domain) and sum per partial row
   SegTables seg;
   unsigned char head_kind[256];
   int B, H, N;

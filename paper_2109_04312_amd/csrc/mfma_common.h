@@ -53,6 +53,33 @@ __device__ inline bf16x8 pack8(const f32x16& x, int c0) {
   return r;
 }
 
+// max / sum of a per-row value across the two lane halves that share the row (lanes l, l ^ 32):
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of the
+// second, so after swapping (x, x) every lane holds both halves' values.
+__device__ inline float half_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Sum of the eight bf16 values of an operand, added to acc (v_dot2 against ones): the row sum
+// of exactly the rounded probabilities that go into the second contraction.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline float sum8(bf16x8 p, float acc) {
+  const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const bf16x2 pr = {p[2 * e], p[2 * e + 1]};
+    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+  }
+  return acc;
+}
+
 __device__ inline bf16x8 lds_read8(const unsigned short* p) {
   return *reinterpret_cast<const bf16x8*>(p);
 }

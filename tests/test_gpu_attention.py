@@ -66,6 +66,19 @@ def test_degenerate_structures(dtype):
     check_workload(w, backward=True)
 
 
+@pytest.mark.parametrize("n_global,N", [(200, 2048), (700, 1500), (1024, 1024), (129, 4000)])
+def test_many_question_tokens(n_global, N):
+    """Question-token owners spanning several 128-row tiles, with and without chunked streams
+    (the all-question case is plain dense attention)."""
+    rng = np.random.default_rng(n_global)
+    R, C = 60, 5
+    row, col, flag = synth.flatten_table(N, n_global, R, C, synth.geometric_lengths(rng, 4.0, 12, R * C))
+    st = synth.Structure(row[None], col[None], flag[None])
+    q, k, v, do = synth.draw_tensors(rng, 1, 2, N, 64, "bf16", 4)
+    w = synth.Workload(f"globals{n_global}", "bf16", st, np.array([ROW, COL], np.uint8), q, k, v, do, 0.125)
+    check_workload(w, backward=True)
+
+
 def test_config2_bf16_fwd_bwd():
     check_workload(synth.make_config(2), backward=True)
 
