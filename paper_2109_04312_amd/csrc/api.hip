@@ -2,6 +2,7 @@
 // stream.  No allocation, no global state.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -38,6 +39,9 @@ mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kin
   a.H = H;
   a.N = N;
   a.scale = scale;
+#ifdef MATE_TRACE
+  if (const char* e = std::getenv("MATE_TRACE_PTR")) a.trace = reinterpret_cast<long long*>(std::strtoull(e, nullptr, 0));
+#endif
   return MATE_OK;
 }
 

@@ -26,19 +26,19 @@ namespace {
 // ======================================================================================
 // dQ (and delta)
 // ======================================================================================
-__global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
+__device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
   // per buffer: K [key][dim], V [key][dim], K^T [dim][key]
   __shared__ __attribute__((aligned(16))) unsigned short lds[2 * 3 * kTileElems];
   __shared__ int q_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return;
+  if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return;
+  if (u.kind == UNIT_NONE) return 0;
 
   const size_t bh = (size_t)id.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
 
   if (u.kind == UNIT_PAD) {
     zero_pad_rows(dQ, u, tid);
-    return;
+    return unit_info(u);
   }
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
   if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
@@ -156,28 +156,33 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
   if (u.part >= 0) {
     const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
     store_partial(dq_acc, a.scale, a.part[0] + slot * BM * kD, wave, lane);
-    return;
+    return unit_info(u);
   }
   store_owned_rows(dq_acc, a.scale, lds, dQ, q_tok, wave, lane);
+  return unit_info(u);
+}
+
+__global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
+  MATE_TRACE_KERNEL(bwd_dq_unit(a), 1)
 }
 
 // ======================================================================================
 // dK, dV
 // ======================================================================================
-__global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
+__device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
   // per buffer: Q [query][dim], dO [query][dim], Q^T [dim][query], dO^T [dim][query]
   __shared__ __attribute__((aligned(16))) unsigned short lds[2 * 4 * kTileElems];
   __shared__ float row_stat[2][2][BN];  // [buffer][lse2 | delta][query]
   __shared__ int k_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return;
+  if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return;
+  if (u.kind == UNIT_NONE) return 0;
 
   const size_t bh = (size_t)id.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
   if (u.kind == UNIT_PAD) {
     zero_pad_rows(dK, u, tid);
     zero_pad_rows(dV, u, tid);
-    return;
+    return unit_info(u);
   }
   // `me` is this lane's key; its window is the set of query slots that see it
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
@@ -321,10 +326,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
     const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
     store_partial(dk_acc, a.scale, a.part[1] + slot * BM * kD, wave, lane);
     store_partial(dv_acc, 1.f, a.part[2] + slot * BM * kD, wave, lane);
-    return;
+    return unit_info(u);
   }
   store_owned_rows(dk_acc, a.scale, lds, dK, k_tok, wave, lane);
   store_owned_rows(dv_acc, 1.f, lds, dV, k_tok, wave, lane);
+  return unit_info(u);
+}
+
+__global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
+  MATE_TRACE_KERNEL(bwd_dkv_unit(a), 2)
 }
 
 // Adds the chunk partials of question-token rows in chunk order and stores dQ, dK, dV rows.

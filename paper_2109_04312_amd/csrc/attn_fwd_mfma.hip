@@ -14,6 +14,7 @@
 // finalize kernel merges with the usual log-sum-exp rule.
 #include <hip/hip_runtime.h>
 
+#include "d2l.h"
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
@@ -21,18 +22,23 @@
 namespace mate {
 namespace {
 
-__global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned short lds[4 * kTileElems];  // 2 x (K, V^T)
+constexpr int NS = 4;                         // tiles in flight + the one being consumed
+constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
+constexpr int kIdxSlots = 8;                  // >= NS + 1 tiles of indices live at once
+
+__device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
+  __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
+  __shared__ int idx_ring[4][kIdxSlots][BN];  // [wavefront][tile & 7][row] token positions
   __shared__ int q_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return;
+  if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return;
+  if (u.kind == UNIT_NONE) return 0;
 
   const size_t bh = (size_t)id.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
@@ -45,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
   if (u.kind == UNIT_PAD) {  // pad positions: O = 0, LSE = 0
     zero_pad_rows(O, u, tid);
     if (tid < BM && u.t0 + tid < u.own_count) LSE[u.own_list[u.t0 + tid]] = 0.f;
-    return;
+    return unit_info(u);
   }
 
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
@@ -60,61 +66,99 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
   f32x16 o_acc[2] = {zero16(), zero16()};
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
-  // wavefronts 0-1 stage K rows, wavefronts 2-3 stage V transposed.  Token indices are fetched
-  // two tiles ahead and rows one tile ahead, so neither latency sits on the critical path.
-  const unsigned short* stage_src = tid < 128 ? K : V;
-  const int sx = tid & 127;
-  auto fetch_idx = [&](TileIdx& ix, int t) {
+  // ---- streaming: K and V tiles go straight from global memory into a ring of NS LDS stages,
+  // NS - 1 tiles ahead of the compute.  The token indices of a tile's 64 rows travel the same
+  // way (one word per lane into a per-wavefront ring), a further NS - 1 tiles ahead, so every
+  // vector load of the loop is asynchronous and the only waits are the explicit ones below.
+  // `since[k]` counts this wavefront's vector loads issued after the data loads of tile
+  // (current + k); index loads are issued just before data loads, so waiting for a tile's
+  // data also retires the index load issued with it.
+  const LoadLane ll = make_load_lane(wave, lane);
+  const int tb = u.t_begin, te = u.t_end;
+  int since[NS];
+#pragma unroll
+  for (int k = 0; k < NS; ++k) since[k] = 0;
+  auto issued = [&](int n) {
+#pragma unroll
+    for (int k = 0; k < NS; ++k) since[k] += n;
+  };
+  auto issue_idx = [&](int t) {
     const int* list; int base, last;
     tile_source(u, global_idx, t, list, base, last);
-    load_tile_idx(ix, list, base, last, sx);
+    issue_row_words(list + min(base + lane, last), &idx_ring[wave][t & (kIdxSlots - 1)][0]);
   };
-  auto store = [&](const TileRegs& r, int buf) {
-    unsigned short* Ks = lds + buf * 2 * kTileElems;
-    if (tid < 128) store_block4x8(r, Ks, nullptr, tid);
-    else store_block4x8(r, nullptr, Ks + kTileElems, tid - 128);
+  auto issue_data = [&](int t) {
+    const int* r = idx_ring[wave][t & (kIdxSlots - 1)];
+    const int x0 = r[ll.row0], x1 = r[ll.row0 + 8];
+    char* st = lds + ((t - tb) % NS) * kStageBytes;
+    issue_tile(K, x0, x1, ll, st, wave);
+    issue_tile(V, x0, x1, ll, st + kTileBytes, wave);
   };
-
-  TileIdx idx;
-  TileRegs regs;
-  fetch_idx(idx, u.t_begin);
-  load_tile_rows(regs, stage_src, idx, sx);
-  if (u.t_begin + 1 < u.t_end) fetch_idx(idx, u.t_begin + 1);
-  store(regs, 0);
-  __syncthreads();
-
-  const int k_off = rho(m) * kLdsRow + hl * 8, v_off = m * kLdsRow + hl * 8;
-  for (int t = u.t_begin; t < u.t_end; ++t) {
-    const int buf = (t - u.t_begin) & 1;
-    const unsigned short* Kp = lds + buf * 2 * kTileElems + k_off;
-    const unsigned short* Vp = lds + buf * 2 * kTileElems + kTileElems + v_off;
-    if (t + 1 < u.t_end) {
-      load_tile_rows(regs, stage_src, idx, sx);
-      if (t + 2 < u.t_end) fetch_idx(idx, t + 2);
+#pragma unroll
+  for (int s = 0; s < 2 * NS - 2; ++s)
+    if (tb + s < te) issue_idx(tb + s);
+  wait_vmcnt_le(0);
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (tb + s < te) {
+      issue_data(tb + s);
+      issued(4);
+      since[s] = 0;
     }
+
+  // Everything loaded into registers so far is pinned as complete here, so that no load with a
+  // register destination is pending inside the loop (the compiler would otherwise wait for
+  // *all* outstanding loads, prefetches included, at the first use).
+  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(me.lo), "v"(me.hi));
+
+  int koff[4], voff[2][2];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = plain_off(m, hl, ks);
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+    voff[db][0] = tr_off(lane, db, 0);
+    voff[db][1] = tr_off(lane, db, 1);
+  }
+
+  for (int t = tb; t < te; ++t) {
+    const int stage = (t - tb) % NS;
+    const char* Kst = lds + stage * kStageBytes;
+    const char* Vst = Kst + kTileBytes;
+    wait_vmcnt_le(since[0]);  // my share of tile t has landed
+    barrier_no_fence();       // ... everyone's has, and everyone is done with tile t - 1
+    if (t + 2 * NS - 2 < te) {
+      issue_idx(t + 2 * NS - 2);
+      issued(1);
+    }
+    if (t + NS - 1 < te) {
+      issue_data(t + NS - 1);
+      issued(4);
+      since[NS - 1] = 0;
+    }
+
     // visible slot window for this tile: question keys [0,G), else this lane's segment range
     const bool part0 = t < u.n_t0;
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
-      // S^T = K Q^T : rows = keys of the tile (permuted by rho), columns = this wave's queries
+      // S^T = K Q^T : rows = keys of the tile, columns = this wave's queries
       f32x16 s[2] = {zero16(), zero16()};
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-          s[jb] = mfma(lds_read8(Kp + jb * 32 * kLdsRow + ks * 16), qf[ks], s[jb]);
+          s[jb] = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s[jb]);
 
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
       if (!full) {  // wave-uniform: some (query, key) pairs of this tile are outside the pattern
         const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 8 * hl - lo;
+        const int d0 = base + 4 * hl - lo;
         const unsigned len = (unsigned)(hi - lo);
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
           for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + jb * 32 + 16 * (c >> 3) + (c & 7)) < len;
+            const bool in = (unsigned)(d0 + jb * 32 + 8 * (c >> 2) + (c & 3)) < len;
             s[jb][c] = in ? s[jb][c] : -INFINITY;
           }
       }
@@ -142,15 +186,17 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
         for (int tt = 0; tt < 2; ++tt) {
           const bf16x8 pb = pack8(s[jb], 8 * tt);
           l_run = sum8(pb, l_run);
+          const char* vt = Vst + (jb * 32 + tt * 16) * 128;
 #pragma unroll
           for (int db = 0; db < 2; ++db)
-            o_acc[db] = mfma(lds_read8(Vp + db * 32 * kLdsRow + jb * 32 + tt * 16), pb, o_acc[db]);
+            o_acc[db] = mfma(read_transposed(vt, voff[db][0], voff[db][1]), pb, o_acc[db]);
         }
       }
     }
-    if (t + 1 < u.t_end) store(regs, buf ^ 1);
-    __syncthreads();
+#pragma unroll
+    for (int k = 0; k + 1 < NS; ++k) since[k] = since[k + 1];
   }
+  __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
 
   const float l_tot = half_sum(l_run);
   if (u.part >= 0) {
@@ -160,10 +206,15 @@ __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
     if (hl == 0)
       *reinterpret_cast<float2*>(a.part_ml + (slot * BM + wave * 32 + m) * 2) =
           make_float2(m_run == -INFINITY ? m_run : m_run * sc, l_tot);
-    return;
+    return unit_info(u);
   }
   if (hl == 0 && me.valid) LSE[me.pos] = (m_run * sc + __builtin_amdgcn_logf(l_tot)) * kLn2;
-  store_owned_rows(o_acc, 1.f / l_tot, lds, O, q_tok, wave, lane);
+  store_owned_rows(o_acc, 1.f / l_tot, reinterpret_cast<unsigned short*>(lds), O, q_tok, wave, lane);
+  return unit_info(u);
+}
+
+__global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
+  MATE_TRACE_KERNEL(fwd_unit(a), 0)
 }
 
 // Merges the chunk partials of question-token queries: O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.

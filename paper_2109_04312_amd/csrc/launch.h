@@ -16,6 +16,7 @@ struct AttnArgs {
   float* part[3];           // partial results of chunked question-token owners, per (b,h):
                             //   forward: [0] unnormalised O;  backward: dQ, dK, dV
   float* part_ml;           // forward: running max (log2 domain) and sum per partial row
+  long long* trace;         // per-workgroup timeline records; only read by MATE_TRACE builds
   SegTables seg;
   unsigned char head_kind[256];
   int B, H, N;

@@ -255,6 +255,28 @@ __device__ inline void zero_pad_rows(unsigned short* __restrict__ out, const Uni
   }
 }
 
+// Development aid (compiled out unless MATE_TRACE is defined): one record per workgroup with
+// its start / end time (100 MHz wall clock), hardware placement and unit description.
+#ifdef MATE_TRACE
+#define MATE_TRACE_KERNEL(body_call, kernel_no)                                            \
+  const long long t_start_ = wall_clock64();                                               \
+  const int info_ = body_call;                                                             \
+  if (a.trace && threadIdx.x == 0) {                                                       \
+    long long* r_ = a.trace + ((size_t)(kernel_no) * (1 << 16) + blockIdx.x) * 4;          \
+    r_[0] = t_start_;                                                                      \
+    r_[1] = wall_clock64();                                                                \
+    r_[2] = info_;                                                                         \
+    r_[3] = ((long long)__builtin_amdgcn_s_getreg(63508) << 32) |                          \
+            (unsigned)__builtin_amdgcn_s_getreg(63492);                                    \
+  }
+#else
+#define MATE_TRACE_KERNEL(body_call, kernel_no) (void)body_call;
+#endif
+// what a unit body reports to the trace: kind | streamed tiles << 4
+__device__ inline int unit_info(const UnitPlan& u) {
+  return u.kind | ((u.kind == UNIT_GLOBAL || u.kind == UNIT_LOCAL ? u.t_end - u.t_begin : 0) << 4);
+}
+
 __device__ inline bool tables_match(const AttnArgs& a) {
   return a.seg.hdr[0] == kMagic && a.seg.hdr[1] == a.B && a.seg.hdr[2] == a.N;
 }

@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmate.so")
+LIB_PATH = os.environ.get("MATE_LIBRARY", os.path.join(_HERE, "libmate.so"))
 
 MATE_OK = 0
 MATE_ERR_NULL, MATE_ERR_SHAPE, MATE_ERR_UNSUPPORTED = -1, -2, -3
