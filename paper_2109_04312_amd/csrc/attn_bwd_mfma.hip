@@ -16,9 +16,11 @@
 // Pairs (table query, table key) are therefore recomputed once in each of the first two.
 #include <hip/hip_runtime.h>
 
+#include "d2l.h"
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
+#include "tile_stream.h"
 
 namespace mate {
 namespace {
@@ -26,15 +28,19 @@ namespace {
 // ======================================================================================
 // dQ (and delta)
 // ======================================================================================
+constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
+constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, lse[64], delta[64]
+
 __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
-  // per buffer: K [key][dim], V [key][dim], K^T [dim][key]
-  __shared__ __attribute__((aligned(16))) unsigned short lds[2 * 3 * kTileElems];
+  __shared__ __attribute__((aligned(1024))) char lds[NS * kDqStage];
+  __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int q_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
   if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
-  const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = a.N, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
@@ -68,46 +74,32 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) delta = fmaf((float)gf[ks][e], (float)of[e], delta);
   }
-  delta += __shfl_xor(delta, 32, 64);
+  delta = half_sum(delta);
   // every chunk of a question-token owner computes the same delta; the first one stores it
   if (hl == 0 && me.valid && u.t_begin == 0) a.delta[bh + me.pos] = delta;
   const float lse2 = a.lse[bh + me.pos] * kLog2e;
   const float sc = a.scale * kLog2e;
 
-  // wavefronts 0-1 stage K (natural + transposed), wavefronts 2-3 stage V (natural); token
-  // indices are fetched two tiles ahead, rows one tile ahead
-  const unsigned short* stage_src = tid < 128 ? K : V;
-  const int sx = tid & 127;
-  auto fetch_idx = [&](TileIdx& ix, int t) {
-    const int* list; int base, last;
-    tile_source(u, global_idx, t, list, base, last);
-    load_tile_idx(ix, list, base, last, sx);
-  };
-  auto store = [&](const TileRegs& r, int buf) {
-    unsigned short* Ks = lds + buf * 3 * kTileElems;
-    if (tid < 128) store_block4x8(r, Ks, Ks + 2 * kTileElems, tid);
-    else store_block4x8(r, Ks + kTileElems, nullptr, tid - 128);
-  };
+  // K and V tiles stream through the LDS ring; K is read both plain (S^T = K Q^T) and
+  // transposed (dQ^T += K^T dS^T), V plain (dP^T = V dO^T).
+  TileStream<kDqStage> stream(u, global_idx, lds, idx_ring[wave], K, V, nullptr, 0, wave, lane);
+  stream.prologue();
+  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(gf[0]), "v"(gf[1]),
+               "v"(gf[2]), "v"(gf[3]), "v"(me.lo), "v"(me.hi), "v"(lse2), "v"(delta));
+
+  int koff[4], toff[2][2];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = plain_off(m, hl, ks);
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+    toff[db][0] = tr_off(lane, db, 0);
+    toff[db][1] = tr_off(lane, db, 1);
+  }
 
   f32x16 dq_acc[2] = {zero16(), zero16()};
-  TileIdx idx;
-  TileRegs regs;
-  fetch_idx(idx, u.t_begin);
-  load_tile_rows(regs, stage_src, idx, sx);
-  if (u.t_begin + 1 < u.t_end) fetch_idx(idx, u.t_begin + 1);
-  store(regs, 0);
-  __syncthreads();
-
-  const int k_off = rho(m) * kLdsRow + hl * 8, t_off = m * kLdsRow + hl * 8;
   for (int t = u.t_begin; t < u.t_end; ++t) {
-    const int buf = (t - u.t_begin) & 1;
-    const unsigned short* Kp = lds + buf * 3 * kTileElems + k_off;
-    const unsigned short* Vp = Kp + kTileElems;
-    const unsigned short* Ktp = lds + buf * 3 * kTileElems + 2 * kTileElems + t_off;
-    if (t + 1 < u.t_end) {
-      load_tile_rows(regs, stage_src, idx, sx);
-      if (t + 2 < u.t_end) fetch_idx(idx, t + 2);
-    }
+    const char* Kst = stream.acquire(t);
+    const char* Vst = Kst + kTileBytes;
     const bool part0 = t < u.n_t0;
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
@@ -117,8 +109,8 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[jb] = mfma(lds_read8(Kp + jb * 32 * kLdsRow + ks * 16), qf[ks], s[jb]);     // S^T  = K Q^T
-          dp[jb] = mfma(lds_read8(Vp + jb * 32 * kLdsRow + ks * 16), gf[ks], dp[jb]);   // dP^T = V dO^T
+          s[jb] = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s[jb]);     // S^T  = K Q^T
+          dp[jb] = mfma(read_plain(Vst + jb * 32 * 128, koff[ks]), gf[ks], dp[jb]);   // dP^T = V dO^T
         }
       // P = exp2(S sc - lse2); dS = P (dP - delta)
 #pragma unroll
@@ -129,13 +121,13 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
       if (!full) {  // wave-uniform: zero the pairs outside the pattern
         const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 8 * hl - lo;
+        const int d0 = base + 4 * hl - lo;
         const unsigned len = (unsigned)(hi - lo);
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
           for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + jb * 32 + 16 * (c >> 3) + (c & 7)) < len;
+            const bool in = (unsigned)(d0 + jb * 32 + 8 * (c >> 2) + (c & 3)) < len;
             s[jb][c] = in ? s[jb][c] : 0.f;
           }
       }
@@ -145,20 +137,21 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const bf16x8 ds8 = pack8(s[jb], 8 * tt);
+          const char* kt = Kst + (jb * 32 + tt * 16) * 128;
 #pragma unroll
           for (int db = 0; db < 2; ++db)
-            dq_acc[db] = mfma(lds_read8(Ktp + db * 32 * kLdsRow + jb * 32 + tt * 16), ds8, dq_acc[db]);
+            dq_acc[db] = mfma(read_transposed(kt, toff[db][0], toff[db][1]), ds8, dq_acc[db]);
         }
     }
-    if (t + 1 < u.t_end) store(regs, buf ^ 1);
-    __syncthreads();
+    stream.release();
   }
+  __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
   if (u.part >= 0) {
     const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
     store_partial(dq_acc, a.scale, a.part[0] + slot * BM * kD, wave, lane);
     return unit_info(u);
   }
-  store_owned_rows(dq_acc, a.scale, lds, dQ, q_tok, wave, lane);
+  store_owned_rows(dq_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dQ, q_tok, wave, lane);
   return unit_info(u);
 }
 
@@ -170,15 +163,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
 // dK, dV
 // ======================================================================================
 __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
-  // per buffer: Q [query][dim], dO [query][dim], Q^T [dim][query], dO^T [dim][query]
-  __shared__ __attribute__((aligned(16))) unsigned short lds[2 * 4 * kTileElems];
-  __shared__ float row_stat[2][2][BN];  // [buffer][lse2 | delta][query]
+  __shared__ __attribute__((aligned(1024))) char lds[NS * kDkvStage];
+  __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int k_tok[BM];
 
   const TileId id = map_block(blockIdx.x, a.B * a.H);
   if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
-  const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = a.N, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
@@ -191,8 +184,6 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
   const unsigned short* dO = static_cast<const unsigned short*>(a.dout) + bh * kD;
   unsigned short* dK = static_cast<unsigned short*>(a.dk) + bh * kD;
   unsigned short* dV = static_cast<unsigned short*>(a.dv) + bh * kD;
-  const float* LSE = a.lse + bh;
-  const float* DELTA = a.delta + bh;
   const int* global_idx = a.seg.global_idx + (size_t)b * N;
 
   if (u.kind == UNIT_PAD) {
@@ -213,52 +204,31 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
   }
   const float sc = a.scale * kLog2e;
 
-  // wavefronts 0-1 stage Q, wavefronts 2-3 stage dO (each natural + transposed);
-  // threads 0..63 / 128..191 also fetch lse / delta of the 64 streamed queries.  Token indices
-  // are fetched two tiles ahead, rows one tile ahead.
-  const unsigned short* stage_src = tid < 128 ? Q : dO;
-  const float* stat_src = tid < 128 ? LSE : DELTA;
-  const float stat_mul = tid < 128 ? kLog2e : 1.f;
-  const int sx = tid & 127;
-  int stat_tok = 0;
-  float stat = 0.f;
-  auto fetch_idx = [&](TileIdx& ix, int t) {
-    const int* list; int base, last;
-    tile_source(u, global_idx, t, list, base, last);
-    load_tile_idx(ix, list, base, last, sx);
-    if (sx < BN) stat_tok = list[min(base + sx, last)];
-  };
-  auto fetch_rows = [&](TileRegs& r, const TileIdx& ix) {
-    load_tile_rows(r, stage_src, ix, sx);
-    if (sx < BN) stat = stat_src[stat_tok] * stat_mul;
-  };
-  auto store = [&](const TileRegs& r, int buf) {
-    unsigned short* Qs = lds + buf * 4 * kTileElems;
-    if (tid < 128) store_block4x8(r, Qs, Qs + 2 * kTileElems, tid);
-    else store_block4x8(r, Qs + kTileElems, Qs + 3 * kTileElems, tid - 128);
-    if (sx < BN) row_stat[buf][tid >> 7][sx] = stat;
-  };
+  // Q and dO tiles of the streamed queries go through the LDS ring, each read plain
+  // (S = Q K^T, dP = dO V^T) and transposed (dK^T += Q^T dS, dV^T += dO^T P); wavefront 0
+  // also brings the queries' lse, wavefront 1 their delta (one float per row).
+  const float* row_src = wave == 0 ? a.lse + bh : wave == 1 ? a.delta + bh : nullptr;
+  TileStream<kDkvStage> stream(u, global_idx, lds, idx_ring[wave], Q, dO, row_src,
+                               2 * kTileBytes + 256 * wave, wave, lane);
+  stream.prologue();
+  asm volatile("" ::"v"(kf[0]), "v"(kf[1]), "v"(kf[2]), "v"(kf[3]), "v"(vf[0]), "v"(vf[1]),
+               "v"(vf[2]), "v"(vf[3]), "v"(me.lo), "v"(me.hi));
+
+  int poff[4], toff[2][2];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) poff[ks] = plain_off(m, hl, ks);
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+    toff[db][0] = tr_off(lane, db, 0);
+    toff[db][1] = tr_off(lane, db, 1);
+  }
 
   f32x16 dk_acc[2] = {zero16(), zero16()}, dv_acc[2] = {zero16(), zero16()};
-  TileIdx idx;
-  TileRegs regs;
-  fetch_idx(idx, u.t_begin);
-  fetch_rows(regs, idx);
-  if (u.t_begin + 1 < u.t_end) fetch_idx(idx, u.t_begin + 1);
-  store(regs, 0);
-  __syncthreads();
-
-  const int n_off = rho(m) * kLdsRow + hl * 8, t_off = m * kLdsRow + hl * 8;
   for (int t = u.t_begin; t < u.t_end; ++t) {
-    const int buf = (t - u.t_begin) & 1;
-    const unsigned short* Qp = lds + buf * 4 * kTileElems + n_off;
-    const unsigned short* Gp = Qp + kTileElems;
-    const unsigned short* Qtp = lds + buf * 4 * kTileElems + 2 * kTileElems + t_off;
-    const unsigned short* Gtp = Qtp + kTileElems;
-    if (t + 1 < u.t_end) {
-      fetch_rows(regs, idx);
-      if (t + 2 < u.t_end) fetch_idx(idx, t + 2);
-    }
+    const char* Qst = stream.acquire(t);
+    const char* Gst = Qst + kTileBytes;
+    const float* lse_row = reinterpret_cast<const float*>(Qst + 2 * kTileBytes);
+    const float* delta_row = lse_row + BN;
     const bool part0 = t < u.n_t0;
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
@@ -268,40 +238,37 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
       for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[ib] = mfma(lds_read8(Qp + ib * 32 * kLdsRow + ks * 16), kf[ks], s[ib]);     // S  = Q K^T
-          dp[ib] = mfma(lds_read8(Gp + ib * 32 * kLdsRow + ks * 16), vf[ks], dp[ib]);   // dP = dO V^T
+          s[ib] = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s[ib]);     // S  = Q K^T
+          dp[ib] = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp[ib]);   // dP = dO V^T
         }
-      // rows of these tiles are the streamed queries: their lse / delta come from LDS, eight
-      // consecutive rows per group of eight registers
+      // rows of these tiles are the streamed queries: their lse / delta come from LDS, four
+      // consecutive rows per group of four registers
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int row0 = ib * 32 + tt * 16 + 8 * hl;
-          const float4 l0 = *reinterpret_cast<const float4*>(&row_stat[buf][0][row0]);
-          const float4 l1 = *reinterpret_cast<const float4*>(&row_stat[buf][0][row0 + 4]);
-          const float4 d0 = *reinterpret_cast<const float4*>(&row_stat[buf][1][row0]);
-          const float4 d1 = *reinterpret_cast<const float4*>(&row_stat[buf][1][row0 + 4]);
-          const float ls[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
-          const float de[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+        for (int g = 0; g < 4; ++g) {
+          const int row0 = ib * 32 + 8 * g + 4 * hl;
+          const float4 l4 = *reinterpret_cast<const float4*>(lse_row + row0);
+          const float4 d4 = *reinterpret_cast<const float4*>(delta_row + row0);
+          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int c = tt * 8 + e;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[ib][c], sc, -ls[e]));
+          for (int r = 0; r < 4; ++r) {
+            const int c = 4 * g + r;
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[ib][c], sc, -kLog2e * ls[r]));
             s[ib][c] = p;                           // P
-            dp[ib][c] = p * (dp[ib][c] - de[e]);    // dS
+            dp[ib][c] = p * (dp[ib][c] - de[r]);    // dS
           }
         }
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
       if (!full) {  // wave-uniform: zero the pairs outside the pattern
         const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 8 * hl - lo;
+        const int d0 = base + 4 * hl - lo;
         const unsigned len = (unsigned)(hi - lo);
 #pragma unroll
         for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
           for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + ib * 32 + 16 * (c >> 3) + (c & 7)) < len;
+            const bool in = (unsigned)(d0 + ib * 32 + 8 * (c >> 2) + (c & 3)) < len;
             s[ib][c] = in ? s[ib][c] : 0.f;
             dp[ib][c] = in ? dp[ib][c] : 0.f;
           }
@@ -311,25 +278,26 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const bf16x8 p8 = pack8(s[ib], 8 * tt), ds8 = pack8(dp[ib], 8 * tt);
+          const char* gt = Gst + (ib * 32 + tt * 16) * 128;
+          const char* qt = Qst + (ib * 32 + tt * 16) * 128;
 #pragma unroll
           for (int db = 0; db < 2; ++db) {
-            const int off = db * 32 * kLdsRow + ib * 32 + tt * 16;
-            dv_acc[db] = mfma(lds_read8(Gtp + off), p8, dv_acc[db]);   // dV^T += dO^T P
-            dk_acc[db] = mfma(lds_read8(Qtp + off), ds8, dk_acc[db]);  // dK^T += Q^T dS
+            dv_acc[db] = mfma(read_transposed(gt, toff[db][0], toff[db][1]), p8, dv_acc[db]);   // dV^T += dO^T P
+            dk_acc[db] = mfma(read_transposed(qt, toff[db][0], toff[db][1]), ds8, dk_acc[db]);  // dK^T += Q^T dS
           }
         }
     }
-    if (t + 1 < u.t_end) store(regs, buf ^ 1);
-    __syncthreads();
+    stream.release();
   }
+  __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
   if (u.part >= 0) {
     const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
     store_partial(dk_acc, a.scale, a.part[1] + slot * BM * kD, wave, lane);
     store_partial(dv_acc, 1.f, a.part[2] + slot * BM * kD, wave, lane);
     return unit_info(u);
   }
-  store_owned_rows(dk_acc, a.scale, lds, dK, k_tok, wave, lane);
-  store_owned_rows(dv_acc, 1.f, lds, dV, k_tok, wave, lane);
+  store_owned_rows(dk_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dK, k_tok, wave, lane);
+  store_owned_rows(dv_acc, 1.f, reinterpret_cast<unsigned short*>(lds), dV, k_tok, wave, lane);
   return unit_info(u);
 }
 

@@ -18,13 +18,12 @@
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
+#include "tile_stream.h"
 
 namespace mate {
 namespace {
 
-constexpr int NS = 4;                         // tiles in flight + the one being consumed
 constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
-constexpr int kIdxSlots = 8;                  // >= NS + 1 tiles of indices live at once
 
 __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
@@ -34,7 +33,8 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
   const TileId id = map_block(blockIdx.x, a.B * a.H);
   if (!id.valid || !tables_match(a)) return 0;
   const int b = id.bh / a.H, h = id.bh % a.H;
-  const int N = a.N, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = a.N, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
   const int view = a.head_kind[h];
   const UnitPlan u = plan_unit(a, b, view, id.tile);
@@ -66,46 +66,10 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
   f32x16 o_acc[2] = {zero16(), zero16()};
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
-  // ---- streaming: K and V tiles go straight from global memory into a ring of NS LDS stages,
-  // NS - 1 tiles ahead of the compute.  The token indices of a tile's 64 rows travel the same
-  // way (one word per lane into a per-wavefront ring), a further NS - 1 tiles ahead, so every
-  // vector load of the loop is asynchronous and the only waits are the explicit ones below.
-  // `since[k]` counts this wavefront's vector loads issued after the data loads of tile
-  // (current + k); index loads are issued just before data loads, so waiting for a tile's
-  // data also retires the index load issued with it.
-  const LoadLane ll = make_load_lane(wave, lane);
+  // ---- streaming: K and V tiles go straight from global memory into a ring of LDS stages
+  TileStream<kStageBytes> stream(u, global_idx, lds, idx_ring[wave], K, V, nullptr, 0, wave, lane);
+  stream.prologue();
   const int tb = u.t_begin, te = u.t_end;
-  int since[NS];
-#pragma unroll
-  for (int k = 0; k < NS; ++k) since[k] = 0;
-  auto issued = [&](int n) {
-#pragma unroll
-    for (int k = 0; k < NS; ++k) since[k] += n;
-  };
-  auto issue_idx = [&](int t) {
-    const int* list; int base, last;
-    tile_source(u, global_idx, t, list, base, last);
-    issue_row_words(list + min(base + lane, last), &idx_ring[wave][t & (kIdxSlots - 1)][0]);
-  };
-  auto issue_data = [&](int t) {
-    const int* r = idx_ring[wave][t & (kIdxSlots - 1)];
-    const int x0 = r[ll.row0], x1 = r[ll.row0 + 8];
-    char* st = lds + ((t - tb) % NS) * kStageBytes;
-    issue_tile(K, x0, x1, ll, st, wave);
-    issue_tile(V, x0, x1, ll, st + kTileBytes, wave);
-  };
-#pragma unroll
-  for (int s = 0; s < 2 * NS - 2; ++s)
-    if (tb + s < te) issue_idx(tb + s);
-  wait_vmcnt_le(0);
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (tb + s < te) {
-      issue_data(tb + s);
-      issued(4);
-      since[s] = 0;
-    }
-
   // Everything loaded into registers so far is pinned as complete here, so that no load with a
   // register destination is pending inside the loop (the compiler would otherwise wait for
   // *all* outstanding loads, prefetches included, at the first use).
@@ -121,20 +85,8 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
   }
 
   for (int t = tb; t < te; ++t) {
-    const int stage = (t - tb) % NS;
-    const char* Kst = lds + stage * kStageBytes;
+    const char* Kst = stream.acquire(t);
     const char* Vst = Kst + kTileBytes;
-    wait_vmcnt_le(since[0]);  // my share of tile t has landed
-    barrier_no_fence();       // ... everyone's has, and everyone is done with tile t - 1
-    if (t + 2 * NS - 2 < te) {
-      issue_idx(t + 2 * NS - 2);
-      issued(1);
-    }
-    if (t + NS - 1 < te) {
-      issue_data(t + NS - 1);
-      issued(4);
-      since[NS - 1] = 0;
-    }
 
     // visible slot window for this tile: question keys [0,G), else this lane's segment range
     const bool part0 = t < u.n_t0;
@@ -193,8 +145,7 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
         }
       }
     }
-#pragma unroll
-    for (int k = 0; k + 1 < NS; ++k) since[k] = since[k + 1];
+    stream.release();
   }
   __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
 
