@@ -31,22 +31,19 @@ namespace {
 constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
 constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, lse[64], delta[64]
 
-__device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
+__device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kDqStage];
   __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int q_tok[BM];
 
-  const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return 0;
-  const int b = id.bh / a.H, h = id.bh % a.H;
+  const int b = w.bh / a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
-  const int view = a.head_kind[h];
-  const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return 0;
+  const int view = w.view;
+  const UnitPlan& u = w.u;
 
-  const size_t bh = (size_t)id.bh * N;
+  const size_t bh = (size_t)w.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
   const unsigned short* K = static_cast<const unsigned short*>(a.k) + bh * kD;
   const unsigned short* V = static_cast<const unsigned short*>(a.v) + bh * kD;
@@ -104,50 +101,46 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
-      f32x16 s[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+      const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
+      const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
+      const int d0 = base + 4 * hl - lo;
+      const unsigned len = (unsigned)(hi - lo);
+      // one 32-key block at a time, so only one block's scores are live
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+      for (int jb = 0; jb < 2; ++jb) {
+        f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[jb] = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s[jb]);     // S^T  = K Q^T
-          dp[jb] = mfma(read_plain(Vst + jb * 32 * 128, koff[ks]), gf[ks], dp[jb]);   // dP^T = V dO^T
+          s = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s);     // S^T  = K Q^T
+          dp = mfma(read_plain(Vst + jb * 32 * 128, koff[ks]), gf[ks], dp);   // dP^T = V dO^T
         }
-      // P = exp2(S sc - lse2); dS = P (dP - delta)
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+        // P = exp2(S sc - lse2); dS = P (dP - delta)
 #pragma unroll
         for (int c = 0; c < 16; ++c)
-          s[jb][c] = __builtin_amdgcn_exp2f(fmaf(s[jb][c], sc, -lse2)) * (dp[jb][c] - delta);
-      const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      if (!full) {  // wave-uniform: zero the pairs outside the pattern
-        const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 4 * hl - lo;
-        const unsigned len = (unsigned)(hi - lo);
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+          s[c] = __builtin_amdgcn_exp2f(fmaf(s[c], sc, -lse2)) * (dp[c] - delta);
+        if (!full) {  // wave-uniform: zero the pairs outside the pattern
 #pragma unroll
           for (int c = 0; c < 16; ++c) {
             const bool in = (unsigned)(d0 + jb * 32 + 8 * (c >> 2) + (c & 3)) < len;
-            s[jb][c] = in ? s[jb][c] : 0.f;
+            s[c] = in ? s[c] : 0.f;
           }
-      }
-      // dQ^T += K^T dS^T
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+        }
+        // dQ^T += K^T dS^T
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 ds8 = pack8(s[jb], 8 * tt);
+          const bf16x8 ds8 = pack8(s, 8 * tt);
           const char* kt = Kst + (jb * 32 + tt * 16) * 128;
 #pragma unroll
           for (int db = 0; db < 2; ++db)
             dq_acc[db] = mfma(read_transposed(kt, toff[db][0], toff[db][1]), ds8, dq_acc[db]);
         }
+      }
     }
     stream.release();
   }
   __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
   if (u.part >= 0) {
-    const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
+    const size_t slot = (size_t)w.bh * owner_slots(N) + u.part;
     store_partial(dq_acc, a.scale, a.part[0] + slot * BM * kD, wave, lane);
     return unit_info(u);
   }
@@ -156,28 +149,29 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a) {
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
-  MATE_TRACE_KERNEL(bwd_dq_unit(a), 1)
+  run_queues(a, 0, [&](const Work& w, int q, int t) {
+    MATE_TRACE_BEGIN
+    const int info = bwd_dq_unit(a, w);
+    MATE_TRACE_END(1, q, t, info)
+  });
 }
 
 // ======================================================================================
 // dK, dV
 // ======================================================================================
-__device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
+__device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kDkvStage];
   __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int k_tok[BM];
 
-  const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return 0;
-  const int b = id.bh / a.H, h = id.bh % a.H;
+  const int b = w.bh / a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
-  const int view = a.head_kind[h];
-  const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return 0;
+  const int view = w.view;
+  const UnitPlan& u = w.u;
 
-  const size_t bh = (size_t)id.bh * N;
+  const size_t bh = (size_t)w.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
   const unsigned short* K = static_cast<const unsigned short*>(a.k) + bh * kD;
   const unsigned short* V = static_cast<const unsigned short*>(a.v) + bh * kD;
@@ -233,18 +227,21 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
-      f32x16 s[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+      const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
+      const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
+      const int d0 = base + 4 * hl - lo;
+      const unsigned len = (unsigned)(hi - lo);
+      // one 32-query block at a time, so only one block's scores are live
 #pragma unroll
-      for (int ib = 0; ib < 2; ++ib)
+      for (int ib = 0; ib < 2; ++ib) {
+        f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[ib] = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s[ib]);     // S  = Q K^T
-          dp[ib] = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp[ib]);   // dP = dO V^T
+          s = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s);     // S  = Q K^T
+          dp = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp);   // dP = dO V^T
         }
-      // rows of these tiles are the streamed queries: their lse / delta come from LDS, four
-      // consecutive rows per group of four registers
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib)
+        // rows of these tiles are the streamed queries: their lse / delta come from LDS, four
+        // consecutive rows per group of four registers
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int row0 = ib * 32 + 8 * g + 4 * hl;
@@ -254,30 +251,22 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const int c = 4 * g + r;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[ib][c], sc, -kLog2e * ls[r]));
-            s[ib][c] = p;                           // P
-            dp[ib][c] = p * (dp[ib][c] - de[r]);    // dS
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[c], sc, -kLog2e * ls[r]));
+            s[c] = p;                       // P
+            dp[c] = p * (dp[c] - de[r]);    // dS
           }
         }
-      const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      if (!full) {  // wave-uniform: zero the pairs outside the pattern
-        const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 4 * hl - lo;
-        const unsigned len = (unsigned)(hi - lo);
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
+        if (!full) {  // wave-uniform: zero the pairs outside the pattern
 #pragma unroll
           for (int c = 0; c < 16; ++c) {
             const bool in = (unsigned)(d0 + ib * 32 + 8 * (c >> 2) + (c & 3)) < len;
-            s[ib][c] = in ? s[ib][c] : 0.f;
-            dp[ib][c] = in ? dp[ib][c] : 0.f;
+            s[c] = in ? s[c] : 0.f;
+            dp[c] = in ? dp[c] : 0.f;
           }
-      }
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib)
+        }
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 p8 = pack8(s[ib], 8 * tt), ds8 = pack8(dp[ib], 8 * tt);
+          const bf16x8 p8 = pack8(s, 8 * tt), ds8 = pack8(dp, 8 * tt);
           const char* gt = Gst + (ib * 32 + tt * 16) * 128;
           const char* qt = Qst + (ib * 32 + tt * 16) * 128;
 #pragma unroll
@@ -286,12 +275,13 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
             dk_acc[db] = mfma(read_transposed(qt, toff[db][0], toff[db][1]), ds8, dk_acc[db]);  // dK^T += Q^T dS
           }
         }
+      }
     }
     stream.release();
   }
   __syncthreads();  // all wavefronts are done reading the stages; reuse them for the epilogue
   if (u.part >= 0) {
-    const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
+    const size_t slot = (size_t)w.bh * owner_slots(N) + u.part;
     store_partial(dk_acc, a.scale, a.part[1] + slot * BM * kD, wave, lane);
     store_partial(dv_acc, 1.f, a.part[2] + slot * BM * kD, wave, lane);
     return unit_info(u);
@@ -302,7 +292,11 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a) {
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
-  MATE_TRACE_KERNEL(bwd_dkv_unit(a), 2)
+  run_queues(a, 1, [&](const Work& w, int q, int t) {
+    MATE_TRACE_BEGIN
+    const int info = bwd_dkv_unit(a, w);
+    MATE_TRACE_END(2, q, t, info)
+  });
 }
 
 // Adds the chunk partials of question-token rows in chunk order and stores dQ, dK, dV rows.
@@ -318,12 +312,24 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
   for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
   const int gt = x / BM, r = x % BM;
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
+  // chunks are read four at a time so that their loads overlap; the order of the additions
+  // is fixed, so the result is deterministic
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int c = 0; c < s.n_chunks; ++c) {
-    const float* p = a.part[which] + ((slot0 + c) * BM + r) * kD + piece * 8;
-    const float4 p0 = *reinterpret_cast<const float4*>(p), p1 = *reinterpret_cast<const float4*>(p + 4);
-    acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
-    acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w;
+  for (int c0 = 0; c0 < s.n_chunks; c0 += 4) {
+    float4 p0[4], p1[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int c = min(c0 + e, s.n_chunks - 1);
+      const float* p = a.part[which] + ((slot0 + c) * BM + r) * kD + piece * 8;
+      p0[e] = *reinterpret_cast<const float4*>(p);
+      p1[e] = *reinterpret_cast<const float4*>(p + 4);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float w = c0 + e < s.n_chunks ? 1.f : 0.f;
+      acc[0] += w * p0[e].x; acc[1] += w * p0[e].y; acc[2] += w * p0[e].z; acc[3] += w * p0[e].w;
+      acc[4] += w * p1[e].x; acc[5] += w * p1[e].y; acc[6] += w * p1[e].z; acc[7] += w * p1[e].w;
+    }
   }
   const int tok = a.seg.global_idx[(size_t)b * N + x];
   void* dst = which == 0 ? a.dq : which == 1 ? a.dk : a.dv;
@@ -340,9 +346,11 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  const dim3 grid(grid_blocks(a.B * a.H, units_per_bh(a.N))), block(kThreads);
+  const dim3 grid(persistent_grid()), block(kThreads);
+  hipError_t e = launch_plan(a, stream);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bwd_dq_mfma_kernel, grid, block, 0, stream, a);
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bwd_dkv_mfma_kernel, grid, block, 0, stream, a);
   e = hipGetLastError();

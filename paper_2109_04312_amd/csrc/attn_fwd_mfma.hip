@@ -25,22 +25,19 @@ namespace {
 
 constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
 
-__device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
+__device__ __forceinline__ int fwd_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
   __shared__ int idx_ring[4][kIdxSlots][BN];  // [wavefront][tile & 7][row] token positions
   __shared__ int q_tok[BM];
 
-  const TileId id = map_block(blockIdx.x, a.B * a.H);
-  if (!id.valid || !tables_match(a)) return 0;
-  const int b = id.bh / a.H, h = id.bh % a.H;
+  const int b = w.bh / a.H;
   const int N = a.N, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int m = lane & 31, hl = lane >> 5;
-  const int view = a.head_kind[h];
-  const UnitPlan u = plan_unit(a, b, view, id.tile);
-  if (u.kind == UNIT_NONE) return 0;
+  const int view = w.view;
+  const UnitPlan& u = w.u;
 
-  const size_t bh = (size_t)id.bh * N;
+  const size_t bh = (size_t)w.bh * N;
   const unsigned short* Q = static_cast<const unsigned short*>(a.q) + bh * kD;
   const unsigned short* K = static_cast<const unsigned short*>(a.k) + bh * kD;
   const unsigned short* V = static_cast<const unsigned short*>(a.v) + bh * kD;
@@ -152,7 +149,7 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
   const float l_tot = half_sum(l_run);
   if (u.part >= 0) {
     // chunk of a question-token owner: leave (unnormalised O, max, sum) for the finalize kernel
-    const size_t slot = (size_t)id.bh * owner_slots(N) + u.part;
+    const size_t slot = (size_t)w.bh * owner_slots(N) + u.part;
     store_partial(o_acc, 1.f, a.part[0] + slot * BM * kD, wave, lane);
     if (hl == 0)
       *reinterpret_cast<float2*>(a.part_ml + (slot * BM + wave * 32 + m) * 2) =
@@ -165,7 +162,11 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a) {
 }
 
 __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
-  MATE_TRACE_KERNEL(fwd_unit(a), 0)
+  run_queues(a, 0, [&](const Work& w, int q, int t) {
+    MATE_TRACE_BEGIN
+    const int info = fwd_unit(a, w);
+    MATE_TRACE_END(0, q, t, info)
+  });
 }
 
 // Merges the chunk partials of question-token queries: O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
@@ -181,17 +182,36 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
   for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
   const int gt = x / BM, r = x % BM;
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
+  // chunks are read several at a time so that their loads overlap (the chunk count is only
+  // known on the device); the combination order is fixed, so the result is deterministic
   float m = -INFINITY;
-  for (int c = 0; c < s.n_chunks; ++c) m = fmaxf(m, a.part_ml[((slot0 + c) * BM + r) * 2]);
+  for (int c0 = 0; c0 < s.n_chunks; c0 += 8) {
+    float mv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      mv[e] = c0 + e < s.n_chunks ? a.part_ml[((slot0 + c0 + e) * BM + r) * 2] : -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m = fmaxf(m, mv[e]);
+  }
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, l = 0.f;
-  for (int c = 0; c < s.n_chunks; ++c) {
-    const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
-    const float w = __builtin_amdgcn_exp2f(ml.x - m);
-    l += w * ml.y;
-    const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
-    const float4 p0 = *reinterpret_cast<const float4*>(p), p1 = *reinterpret_cast<const float4*>(p + 4);
-    acc[0] += w * p0.x; acc[1] += w * p0.y; acc[2] += w * p0.z; acc[3] += w * p0.w;
-    acc[4] += w * p1.x; acc[5] += w * p1.y; acc[6] += w * p1.z; acc[7] += w * p1.w;
+  for (int c0 = 0; c0 < s.n_chunks; c0 += 4) {
+    float2 ml[4];
+    float4 p0[4], p1[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int c = min(c0 + e, s.n_chunks - 1);
+      ml[e] = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
+      const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
+      p0[e] = *reinterpret_cast<const float4*>(p);
+      p1[e] = *reinterpret_cast<const float4*>(p + 4);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float w = c0 + e < s.n_chunks ? __builtin_amdgcn_exp2f(ml[e].x - m) : 0.f;
+      l += w * ml[e].y;
+      acc[0] += w * p0[e].x; acc[1] += w * p0[e].y; acc[2] += w * p0[e].z; acc[3] += w * p0[e].w;
+      acc[4] += w * p1[e].x; acc[5] += w * p1[e].y; acc[6] += w * p1[e].z; acc[7] += w * p1[e].w;
+    }
   }
   const float inv = 1.f / l;
   const int tok = a.seg.global_idx[(size_t)b * N + x];
@@ -209,9 +229,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(fwd_mfma_kernel, dim3(grid_blocks(a.B * a.H, units_per_bh(a.N))),
-                     dim3(kThreads), 0, stream, a);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_plan(a, stream);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fwd_mfma_kernel, dim3(persistent_grid()), dim3(kThreads), 0, stream, a);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   // partials exist only while question tokens fill at most half the owner slots; a few
   // workgroups per (b,h) stride over however many question tokens there are

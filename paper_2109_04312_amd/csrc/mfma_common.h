@@ -112,22 +112,4 @@ __device__ inline uint2 transpose_pick(const uint4 r[4], int e) {
   return o;
 }
 
-// Work distribution.  Consecutive workgroup ids land on different XCDs (8 of them, each with
-// its own L2).  All tiles of one (sequence, head) are given ids congruent mod 8 so they share
-// an L2; tile 0 of every (b, h) comes first, then tile 1, ... so long tiles start early.
-struct TileId {
-  int bh, tile;
-  bool valid;
-};
-__device__ inline TileId map_block(int bid, int BH) {
-  const int groups = (BH + 7) >> 3;
-  const int xcd = bid & 7, slot = bid >> 3;
-  TileId t;
-  t.bh = (slot % groups) * 8 + xcd;
-  t.tile = slot / groups;
-  t.valid = t.bh < BH;
-  return t;
-}
-inline int grid_blocks(int BH, int tiles) { return ((BH + 7) >> 3) * 8 * tiles; }
-
 }  // namespace mate

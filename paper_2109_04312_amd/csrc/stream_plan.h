@@ -5,14 +5,17 @@
 // are symmetric: an owned table token meets the question tokens plus the table tokens of its
 // own row / column segment; an owned question token meets every non-pad token.
 //
-// Units per (sequence, head), in launch order (longest first, surplus last):
-//   [0, n_lt)          table-token owners, 128 consecutive slots of the head kind's sorted order
-//   then n_pt          pad owners (zero fill);  n_lt + n_pt <= UG + 1
-//   [UG + 1, 2 UG + 1) question-token owners.  Their streamed side is the whole sequence, so it
-//                      is cut into chunks of >= kMinChunkTiles tiles that run as separate
-//                      workgroups and leave partial results, merged by a finalize kernel.
-// with UG = ceil(N / 128).  G, L, P live on the device, so the host launches the worst case
-// (2 * UG + 1 units) and surplus workgroups exit at once.
+// Units of one (sequence, head):
+//   local   n_lt = ceil(L / 128) table-token owners, 128 consecutive slots of the head kind's
+//           sorted order
+//   global  question-token owners.  Their streamed side is the whole sequence, so it is cut into
+//           chunks of >= kMinChunkTiles tiles that run as separate units and leave partial
+//           results, merged by a finalize kernel.  n_gt * n_chunks <= UG = ceil(N / 128).
+//   pad     n_pt = ceil(P / 128) pad owners (zero fill)
+// G, L, P live on the device, so a small plan kernel counts the units and lays them out in
+// eight work queues (one per XCD, so that the units of one (sequence, head) share an L2),
+// longest kind of unit first; persistent workgroups pull tickets from the queue of their own
+// XCD and steal from the others when it runs dry.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,12 +27,10 @@ namespace mate {
 constexpr int BM = 128;            // owned rows per workgroup (32 per wavefront)
 constexpr int BN = 64;             // streamed rows per tile
 constexpr int kThreads = 256;
-constexpr int kTileElems = BN * kLdsRow;
 constexpr int kFinalizeBlocks = 4; // workgroups per (b,h) in the finalize kernels (32 rows each, strided)
 constexpr int kMinChunkTiles = 8;  // streamed tiles per chunk of a question-token owner
 
 __host__ __device__ inline int owner_slots(int N) { return (N + BM - 1) / BM; }  // UG
-inline int units_per_bh(int N) { return 2 * owner_slots(N) + 1; }
 
 // How the streamed side of question-token owners is chunked (same answer in every kernel).
 struct GlobalSplit {
@@ -50,6 +51,20 @@ __device__ inline GlobalSplit global_split(int G, int L, int N) {
   return s;
 }
 
+// ---- plan buffer (ints, in the caller's workspace) -------------------------------------------
+//   [0, 16)            ticket counters: [kernel slot 0..1][queue 0..7]
+//   [24]               first_view: the view whose table-token units stream more tiles
+//   [32 + 8 q + band]  number of units of queue q in bands 0..band (inclusive prefix), band < 4:
+//                      0 local units of first_view heads, 1 local units of the other heads,
+//                      2 question-token units, 3 pad units
+//   [96 + ((4 q + band) (nq + 1)) + j]  exclusive prefix over the queue's (b,h) pairs
+//                      bh = q + 8 j, j < nq = ceil(B H / 8), of their units in that band
+constexpr int kPlanCounters = 0, kPlanFirstView = 24, kPlanCum = 32, kPlanPref = 96;
+__host__ __device__ inline int plan_nq(int BH) { return (BH + 7) >> 3; }
+__host__ __device__ inline size_t plan_words(int BH) {
+  return (size_t)kPlanPref + 32 * (size_t)(plan_nq(BH) + 1);
+}
+
 enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
 
 struct UnitPlan {
@@ -65,8 +80,7 @@ struct UnitPlan {
   int G, L, P;
 };
 
-__device__ inline UnitPlan plan_unit(const AttnArgs& a, int b, int view, int unit) {
-  const int N = a.N;
+__device__ inline UnitPlan plan_base(const AttnArgs& a, int b) {
   const int* cnt = a.seg.counts + (size_t)b * kCountWords;
   UnitPlan u;
   u.kind = UNIT_NONE;
@@ -75,45 +89,129 @@ __device__ inline UnitPlan plan_unit(const AttnArgs& a, int b, int view, int uni
   u.P = cnt[C_P];
   u.part = -1;
   u.n_t0 = (u.G + BN - 1) / BN;
-  const int UG = owner_slots(N);
-  if (unit > UG) {
-    unit -= UG + 1;
-    const GlobalSplit s = global_split(u.G, u.L, N);
-    if (s.n_gt == 0) return u;
-    const int gt = unit / s.n_chunks, c = unit % s.n_chunks;
-    if (gt >= s.n_gt) return u;
-    u.kind = UNIT_GLOBAL;
-    u.t0 = gt * BM;
-    u.own_list = a.seg.global_idx + (size_t)b * N;
-    u.own_count = u.G;
-    u.str_list = a.seg.perm[0] + (size_t)b * N;  // row order: the contiguous one
-    u.s_lo = 0;
-    u.s_hi = u.L;
-    u.t_begin = c * s.per;
-    u.t_end = min(s.n_st, u.t_begin + s.per);
-    if (s.n_chunks > 1) u.part = unit;
-    return u;
-  }
-  const int n_lt = (u.L + BM - 1) / BM, n_pt = (u.P + BM - 1) / BM;
-  const int t = unit;
-  if (t < n_lt) {
-    u.kind = UNIT_LOCAL;
-    u.t0 = t * BM;
-    u.own_list = a.seg.perm[view] + (size_t)b * N;
-    u.own_count = u.L;
-    u.str_list = u.own_list;
-    const int2* rng = a.seg.slot_rng[view] + (size_t)b * N;
-    u.s_lo = rng[u.t0].x;
-    u.s_hi = rng[min(u.t0 + BM, u.L) - 1].y;
-    u.t_begin = 0;
-    u.t_end = u.n_t0 + (u.s_hi - u.s_lo + BN - 1) / BN;
-  } else if (t < n_lt + n_pt) {
-    u.kind = UNIT_PAD;
-    u.t0 = (t - n_lt) * BM;
-    u.own_list = a.seg.pad_idx + (size_t)b * N;
-    u.own_count = u.P;
-  }
+  u.t_begin = u.t_end = 0;
   return u;
+}
+// Table-token owner number `tile` of (b, view).
+__device__ inline UnitPlan plan_local(const AttnArgs& a, int b, int view, int tile) {
+  UnitPlan u = plan_base(a, b);
+  const int N = a.N;
+  u.kind = UNIT_LOCAL;
+  u.t0 = tile * BM;
+  u.own_list = a.seg.perm[view] + (size_t)b * N;
+  u.own_count = u.L;
+  u.str_list = u.own_list;
+  const int2* rng = a.seg.slot_rng[view] + (size_t)b * N;
+  u.s_lo = rng[u.t0].x;
+  u.s_hi = rng[min(u.t0 + BM, u.L) - 1].y;
+  u.t_end = u.n_t0 + (u.s_hi - u.s_lo + BN - 1) / BN;
+  return u;
+}
+// Question-token unit number `gu` of sequence b: owner tile gu / n_chunks, chunk gu % n_chunks.
+__device__ inline UnitPlan plan_global(const AttnArgs& a, int b, int gu) {
+  UnitPlan u = plan_base(a, b);
+  const int N = a.N;
+  const GlobalSplit s = global_split(u.G, u.L, N);
+  const int gt = gu / s.n_chunks, c = gu % s.n_chunks;
+  u.kind = UNIT_GLOBAL;
+  u.t0 = gt * BM;
+  u.own_list = a.seg.global_idx + (size_t)b * N;
+  u.own_count = u.G;
+  u.str_list = a.seg.perm[0] + (size_t)b * N;  // row order: the contiguous one
+  u.s_lo = 0;
+  u.s_hi = u.L;
+  u.t_begin = c * s.per;
+  u.t_end = min(s.n_st, u.t_begin + s.per);
+  if (s.n_chunks > 1) u.part = gu;
+  return u;
+}
+__device__ inline UnitPlan plan_pad(const AttnArgs& a, int b, int tile) {
+  UnitPlan u = plan_base(a, b);
+  u.kind = UNIT_PAD;
+  u.t0 = tile * BM;
+  u.own_list = a.seg.pad_idx + (size_t)b * a.N;
+  u.own_count = u.P;
+  return u;
+}
+
+// Development aid (compiled out unless MATE_TRACE is defined): one record per unit with its
+// start / end time (100 MHz wall clock), hardware placement and description.
+#ifdef MATE_TRACE
+#define MATE_TRACE_BEGIN const long long t_start_ = wall_clock64();
+#define MATE_TRACE_END(kernel_no, q, t, info)                                              \
+  if (a.trace && threadIdx.x == 0 && (t) < 8192) {                                         \
+    long long* r_ = a.trace + ((size_t)(kernel_no) * (1 << 16) + (q) * 8192 + (t)) * 4;    \
+    r_[0] = t_start_;                                                                      \
+    r_[1] = wall_clock64();                                                                \
+    r_[2] = (info);                                                                        \
+    r_[3] = ((long long)__builtin_amdgcn_s_getreg(63508) << 32) |                          \
+            (unsigned)__builtin_amdgcn_s_getreg(63492);                                    \
+  }
+#else
+#define MATE_TRACE_BEGIN
+#define MATE_TRACE_END(kernel_no, q, t, info) (void)(info);
+#endif
+
+// ---- work queues -------------------------------------------------------------------------------
+struct Work {
+  int bh, view;
+  UnitPlan u;
+};
+
+__device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7; }  // XCC_ID[3:0]
+
+// Unit number `t` of queue `q` -> which (b,h), which unit.  All inputs wave-uniform.
+__device__ inline Work decode_ticket(const AttnArgs& a, int q, int t) {
+  const int BH = a.B * a.H, nq = plan_nq(BH);
+  const int* cum = a.plan + kPlanCum + 8 * q;
+  int band = 0, r = t;
+  while (band < 3 && t >= cum[band]) ++band;
+  if (band) r = t - cum[band - 1];
+  const int* pref = a.plan + kPlanPref + (4 * q + band) * (nq + 1);
+  int lo = 0, hi = nq;  // largest j with pref[j] <= r
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (pref[mid] <= r) lo = mid; else hi = mid;
+  }
+  Work w;
+  w.bh = q + 8 * lo;
+  const int unit = r - pref[lo];
+  const int b = w.bh / a.H, h = w.bh % a.H;
+  w.view = a.head_kind[h];
+  if (band < 2) w.u = plan_local(a, b, w.view, unit);
+  else if (band == 2) w.u = plan_global(a, b, unit);
+  else w.u = plan_pad(a, b, unit);
+  return w;
+}
+
+// Persistent workgroup: pull tickets from the queue of this workgroup's XCD, then from the
+// others; `body(work, queue, ticket)` must leave LDS reusable for the next unit when it returns.
+template <typename Body>
+__device__ inline void run_queues(const AttnArgs& a, int kernel_slot, Body body) {
+  __shared__ int s_ticket, s_queue;
+  int* counters = a.plan + kPlanCounters + 8 * kernel_slot;
+  int q = xcc_id(), tried = 0;
+  for (;;) {
+    __syncthreads();  // the previous unit is completely done with LDS, s_ticket and s_queue
+    if (threadIdx.x == 0) {
+      int t = -1;
+      while (tried < 8) {
+        t = atomicAdd(&counters[q], 1);
+        if (t < a.plan[kPlanCum + 8 * q + 3]) break;
+        q = (q + 1) & 7;
+        ++tried;
+        t = -1;
+      }
+      s_ticket = t;
+      s_queue = q;
+    }
+    __syncthreads();
+    // wave-uniform values: keep the whole unit description in scalar registers
+    const int t = __builtin_amdgcn_readfirstlane(s_ticket);
+    const int tq = __builtin_amdgcn_readfirstlane(s_queue);
+    if (t < 0) return;
+    body(decode_ticket(a, tq, t), tq, t);
+  }
 }
 
 // Streamed tile t of a unit: which index list, first slot, last valid slot.
@@ -152,55 +250,6 @@ __device__ inline OwnedRow owned_row(const UnitPlan& u, const AttnArgs& a, int b
   r.a_lo = __builtin_amdgcn_readlane(r.lo, 31);
   r.a_hi = __builtin_amdgcn_readlane(r.hi, 0);
   return r;
-}
-
-struct TileRegs {
-  uint4 r[4];
-};
-struct TileIdx {
-  int tok[4];
-};
-
-// Staging a streamed tile is split in two so that the index loads of tile t+2 are in flight
-// while tile t+1's rows are fetched: x in [0,128) names a (4 rows x 8 dims) block.
-__device__ inline void load_tile_idx(TileIdx& ix, const int* __restrict__ list, int base,
-                                     int last, int x) {
-  const int jg = x & 15;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) ix.tok[u] = list[min(base + jg * 4 + u, last)];
-}
-__device__ inline void load_tile_rows(TileRegs& t, const unsigned short* __restrict__ X,
-                                      const TileIdx& ix, int x) {
-  const int dg = x >> 4;
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-    t.r[u] = *reinterpret_cast<const uint4*>(X + (size_t)ix.tok[u] * kD + dg * 8);
-}
-
-// 128 threads fetch a 64-row x 64-dim tile as (4 rows x 8 dims) blocks; x in [0,128).
-__device__ inline void load_block4x8(TileRegs& t, const unsigned short* __restrict__ X,
-                                     const int* __restrict__ list, int base, int last, int x) {
-  const int jg = x & 15, dg = x >> 4;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int tok = list[min(base + jg * 4 + u, last)];
-    t.r[u] = *reinterpret_cast<const uint4*>(X + (size_t)tok * kD + dg * 8);
-  }
-}
-// ... and write it to LDS as [row][dim] (nat) and / or transposed as [dim][row] (tr).
-__device__ inline void store_block4x8(const TileRegs& t, unsigned short* nat, unsigned short* tr,
-                                      int x) {
-  const int jg = x & 15, dg = x >> 4;
-  if (nat) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      *reinterpret_cast<uint4*>(nat + (jg * 4 + u) * kLdsRow + dg * 8) = t.r[u];
-  }
-  if (tr) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      *reinterpret_cast<uint2*>(tr + (dg * 8 + e) * kLdsRow + jg * 4) = transpose_pick(t.r, e);
-  }
 }
 
 // Final results: a C tile pair (columns = owned rows, registers = head dims) scaled, rounded to
@@ -255,23 +304,6 @@ __device__ inline void zero_pad_rows(unsigned short* __restrict__ out, const Uni
   }
 }
 
-// Development aid (compiled out unless MATE_TRACE is defined): one record per workgroup with
-// its start / end time (100 MHz wall clock), hardware placement and unit description.
-#ifdef MATE_TRACE
-#define MATE_TRACE_KERNEL(body_call, kernel_no)                                            \
-  const long long t_start_ = wall_clock64();                                               \
-  const int info_ = body_call;                                                             \
-  if (a.trace && threadIdx.x == 0) {                                                       \
-    long long* r_ = a.trace + ((size_t)(kernel_no) * (1 << 16) + blockIdx.x) * 4;          \
-    r_[0] = t_start_;                                                                      \
-    r_[1] = wall_clock64();                                                                \
-    r_[2] = info_;                                                                         \
-    r_[3] = ((long long)__builtin_amdgcn_s_getreg(63508) << 32) |                          \
-            (unsigned)__builtin_amdgcn_s_getreg(63492);                                    \
-  }
-#else
-#define MATE_TRACE_KERNEL(body_call, kernel_no) (void)body_call;
-#endif
 // what a unit body reports to the trace: kind | streamed tiles << 4
 __device__ inline int unit_info(const UnitPlan& u) {
   return u.kind | ((u.kind == UNIT_GLOBAL || u.kind == UNIT_LOCAL ? u.t_end - u.t_begin : 0) << 4);
