@@ -27,6 +27,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 D = 64
+# HBM bytes per launch on the headline workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (summaries and the scaling against a copy kernel are under profiles/); None = not measured
+TRAFFIC = {}
 
 
 def useful_pairs_per_view(st):
@@ -101,14 +104,10 @@ def main():
     ws_b = mate.workspace(B, H, N, D, code, True, dev)
     hk = w.head_kind
 
-    def step(ev=None):
-        if ev: ev[0].record()
+    def step():
         mate.build_segments(row, col, flg, out=seg)
-        if ev: ev[1].record()
         mate.attn_fwd(q, k, v, seg, hk, w.scale, out=out, lse=lse, ws=ws_f)
-        if ev: ev[2].record()
         mate.attn_bwd(q, k, v, out, lse, do, seg, hk, w.scale, dq=dq, dk=dk, dv=dv, ws=ws_b)
-        if ev: ev[3].record()
 
     for _ in range(args.warmup):
         step()
@@ -120,25 +119,50 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
 
-    # second pass of the same loop with HIP events between the calls (current stream = the
-    # stream the kernels run on): per-call device time
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    for e in evs:
-        step(e)
+    # second pass of the same loop: HIP events recorded by the library around ONE kernel launch
+    # per step (on the stream the kernels run on), cycling through the kernels
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    def new_event():
+        ev = C.c_void_p()
+        assert hip.hipEventCreate(C.byref(ev)) == 0
+        return ev
+    kernels = {"build_segments": mate.MATE_KERNEL_BUILD, "attn_fwd": mate.MATE_KERNEL_FWD,
+               "attn_bwd_dq": mate.MATE_KERNEL_BWD_DQ, "attn_bwd_dkv": mate.MATE_KERNEL_BWD_DKV}
+    per_kernel = max(5, args.steps // len(kernels))
+    pairs_ev = {name: [(new_event(), new_event()) for _ in range(per_kernel)] for name in kernels}
+    t1 = time.perf_counter()
+    for i in range(per_kernel):
+        for name, kid in kernels.items():
+            e0, e1 = pairs_ev[name][i]
+            assert mate.mate_profile_kernel(kid, e0, e1) == 0
+            step()
     torch.cuda.synchronize()
-    t_build = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3
-    t_fwd = float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e-3
-    t_bwd = float(np.mean([e[2].elapsed_time(e[3]) for e in evs])) * 1e-3
+    ms_per_step_pass2 = 1e3 * (time.perf_counter() - t1) / (per_kernel * len(kernels))
+    kernel_s = {}
+    for name in kernels:
+        tot = 0.0
+        for e0, e1 in pairs_ev[name]:
+            ms = C.c_float()
+            assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
+            tot += ms.value
+        kernel_s[name] = tot / per_kernel * 1e-3
+    t_build, t_fwd = kernel_s["build_segments"], kernel_s["attn_fwd"]
+    t_dq, t_dkv = kernel_s["attn_bwd_dq"], kernel_s["attn_bwd_dkv"]
 
     pv = useful_pairs_per_view(st)
     pairs = int(sum(pv[b, int(hk[h])] for b in range(B) for h in range(H)))
     tokens = B * N
     nonpad = int((st.flags != synth.TOK_PAD).sum())
     value = tokens / (elapsed / args.steps)
-    fl_fwd, fl_bwd = 4 * D * pairs, 10 * D * pairs
-    cand = {"mate_attn_fwd": (fl_fwd, t_fwd), "mate_attn_bwd": (fl_bwd, t_bwd)}
+    # algorithmic flop per useful pair: forward 4*D (QK^T, PV); backward 10*D, of which the dQ
+    # kernel is credited S, dP and dQ (6*D) and the dK/dV kernel dV and dK (4*D) -- its own
+    # recomputation of S and dP is not algorithmic work
+    cand = {"fwd_mfma_kernel": (4 * D * pairs, t_fwd), "bwd_dq_mfma_kernel": (6 * D * pairs, t_dq),
+            "bwd_dkv_mfma_kernel": (4 * D * pairs, t_dkv)}
     dom = max(cand, key=lambda n: cand[n][1])
     ach = cand[dom][0] / cand[dom][1] / 1e12
+    t_attn = ms_per_step * 1e-3 - t_build
 
     res = {
         "metric": "MATE attn fwd+bwd tokens/s & useful-pair TFLOP/s, seq 8192, 16 heads, 1 GPU",
@@ -149,12 +173,15 @@ def main():
                    "col_heads": int((hk == 1).sum()), "non_pad_tokens": nonpad, "useful_pairs": pairs,
                    "step": "mate_build_segments + mate_attn_fwd + mate_attn_bwd"},
         "useful_tflops": 14 * D * pairs / (elapsed / args.steps) / 1e12,
-        "useful_tflops_attn_only": 14 * D * pairs / (t_fwd + t_bwd) / 1e12,
-        "tokens_per_s_attn_only": tokens / (t_fwd + t_bwd),
-        "device_ms": {"build_segments": t_build * 1e3, "attn_fwd": t_fwd * 1e3, "attn_bwd": t_bwd * 1e3},
+        "useful_tflops_attn_only": 14 * D * pairs / t_attn / 1e12,
+        "tokens_per_s_attn_only": tokens / t_attn,
+        "kernel_ms": {k: v * 1e3 for k, v in kernel_s.items()},
+        "ms_per_step_event_pass": ms_per_step_pass2,
         "flop_convention": "fwd 4*D, bwd 10*D flop per useful (query,key) pair; exp not counted",
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None},
+                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC.get(dom),
+                     "algorithmic_flop_per_launch": cand[dom][0],
+                     "avg_launch_us": cand[dom][1] * 1e6},
         "segment_builder": {"us": t_build * 1e6, "keys_per_s": 2 * tokens / t_build,
                             "algorithmic_GBps": 30.0 * tokens / t_build / 1e9,
                             "frac_hbm": 30.0 * tokens / t_build / 1e9 / PEAK_HBM_GBS},

@@ -145,6 +145,18 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
                           float scale, void* dq, void* dk, void* dv, void* workspace,
                           size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement hook, not part of the computation: arms the calling thread so that the next
+ * launch of the named kernel (inside mate_build_segments / mate_attn_fwd / mate_attn_bwd) is
+ * bracketed by hipEventRecord(start_event) and hipEventRecord(stop_event) on the stream of that
+ * call; the hook disarms itself once used.  The events are hipEvent_t handles passed as void*,
+ * created with timing enabled and owned by the caller.  kernel = MATE_KERNEL_NONE disarms.
+ * This is the only state the library keeps (per host thread).
+ */
+enum { MATE_KERNEL_NONE = 0, MATE_KERNEL_BUILD = 1, MATE_KERNEL_FWD = 2, MATE_KERNEL_BWD_DQ = 3,
+       MATE_KERNEL_BWD_DKV = 4 };
+mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event);
+
 /* Static, NUL-terminated description of a status code (HOST pointer, never NULL). */
 const char* mate_status_string(mate_status s);
 

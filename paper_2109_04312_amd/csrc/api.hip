@@ -13,6 +13,12 @@
 
 using namespace mate;
 
+namespace mate {
+// Measurement hook (see mate_profile_kernel): events to record around the next launch of one
+// kernel.  Thread-local, cleared when used.
+thread_local ProfileHook g_profile_hook = {0, nullptr, nullptr};
+}  // namespace mate
+
 namespace {
 
 bool shape_ok(int B, int N) { return B >= 1 && N >= 1 && N <= MATE_MAX_N; }
@@ -158,6 +164,15 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = (t == MATE_BF16) ? launch_bwd_mfma(a, s) : launch_bwd_scalar(a, false, s);
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event) {
+  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_BWD_DKV) return MATE_ERR_UNSUPPORTED;
+  if (kernel != MATE_KERNEL_NONE && (!start_event || !stop_event)) return MATE_ERR_NULL;
+  g_profile_hook.kernel = kernel;
+  g_profile_hook.start = static_cast<hipEvent_t>(start_event);
+  g_profile_hook.stop = static_cast<hipEvent_t>(stop_event);
+  return MATE_OK;
 }
 
 const char* mate_status_string(mate_status s) {

@@ -349,10 +349,16 @@ hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
   const dim3 grid(persistent_grid()), block(kThreads);
   hipError_t e = launch_plan(a, stream);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dq_mfma_kernel, grid, block, 0, stream, a);
+  {
+    ProfileScope prof(3, stream);
+    hipLaunchKernelGGL(bwd_dq_mfma_kernel, grid, block, 0, stream, a);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, grid, block, 0, stream, a);
+  {
+    ProfileScope prof(4, stream);
+    hipLaunchKernelGGL(bwd_dkv_mfma_kernel, grid, block, 0, stream, a);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (owner_slots(a.N) >= 2)  // partials exist only while question tokens fill <= half the owner slots

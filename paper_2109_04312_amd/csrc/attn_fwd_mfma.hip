@@ -231,7 +231,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
   hipError_t e = launch_plan(a, stream);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fwd_mfma_kernel, dim3(persistent_grid()), dim3(kThreads), 0, stream, a);
+  {
+    ProfileScope prof(2, stream);
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(persistent_grid()), dim3(kThreads), 0, stream, a);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   // partials exist only while question tokens fill at most half the owner slots; a few

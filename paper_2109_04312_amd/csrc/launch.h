@@ -24,6 +24,27 @@ struct AttnArgs {
   float scale;
 };
 
+// Measurement hook: when `kernel` matches the kernel about to be launched, record `start`
+// before and `stop` after that one launch on its stream, then disarm.
+struct ProfileHook {
+  int kernel;
+  hipEvent_t start, stop;
+};
+extern thread_local ProfileHook g_profile_hook;
+struct ProfileScope {
+  hipStream_t stream;
+  bool armed;
+  ProfileScope(int kernel, hipStream_t s) : stream(s), armed(g_profile_hook.kernel == kernel) {
+    if (armed) (void)hipEventRecord(g_profile_hook.start, stream);
+  }
+  ~ProfileScope() {
+    if (armed) {
+      (void)hipEventRecord(g_profile_hook.stop, stream);
+      g_profile_hook.kernel = 0;
+    }
+  }
+};
+
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
                                  const unsigned char* flags, int B, int N, int* seg,
                                  hipStream_t stream);

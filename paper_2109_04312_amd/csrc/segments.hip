@@ -177,6 +177,7 @@ hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
                                  const unsigned char* flags, int B, int N, int* seg,
                                  hipStream_t stream) {
   dim3 grid(B, 2), block(kSegThreads);
+  ProfileScope prof(1, stream);
 #define MATE_SEG_CASE(P2)                                                                  \
   if (N <= P2) {                                                                            \
     hipLaunchKernelGGL(build_segments_kernel<P2>, grid, block, 0, stream, row_ids, col_ids, \

@@ -26,7 +26,10 @@ MATE_HEAD_ROW, MATE_HEAD_COL = 0, 1
 MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
-           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_status_string"]
+           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_profile_kernel",
+           "mate_status_string"]
+MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
+MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2109_04312_amd.build` "
@@ -47,6 +50,8 @@ _lib.mate_attn_fwd.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _
 _lib.mate_attn_bwd.restype = _i
 _lib.mate_attn_bwd.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
                                _p, _p, _p, _p, _sz, _p]
+_lib.mate_profile_kernel.restype = _i
+_lib.mate_profile_kernel.argtypes = [_i, _p, _p]
 _lib.mate_status_string.restype = C.c_char_p
 _lib.mate_status_string.argtypes = [_i]
 
@@ -56,6 +61,7 @@ mate_build_segments = _lib.mate_build_segments
 mate_segments_export = _lib.mate_segments_export
 mate_attn_fwd = _lib.mate_attn_fwd
 mate_attn_bwd = _lib.mate_attn_bwd
+mate_profile_kernel = _lib.mate_profile_kernel
 
 
 def mate_status_string(status: int) -> str:
