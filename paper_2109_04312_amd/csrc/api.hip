@@ -110,7 +110,7 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
       counts[3 * b + 1] = c[C_L];
       counts[3 * b + 2] = c[C_SROW + view];
     }
-    bad |= c[5] | c[6];
+    bad |= c[5] | c[6];  // per-view "bad id or flag seen" words
   }
   return bad ? MATE_ERR_BAD_ID : MATE_OK;
 }

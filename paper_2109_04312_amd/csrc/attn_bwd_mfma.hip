@@ -149,11 +149,12 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a, const Work& w) {
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
-  run_queues(a, 0, [&](const Work& w, int q, int t) {
-    MATE_TRACE_BEGIN
-    const int info = bwd_dq_unit(a, w);
-    MATE_TRACE_END(1, q, t, info)
-  });
+  Work w;
+  int queue, ticket;
+  if (!take_unit(a, 0, w, queue, ticket)) return;
+  MATE_TRACE_BEGIN
+  const int info = bwd_dq_unit(a, w);
+  MATE_TRACE_END(1, queue, ticket, info)
 }
 
 // ======================================================================================
@@ -292,11 +293,12 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a, const Work& w) {
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
-  run_queues(a, 1, [&](const Work& w, int q, int t) {
-    MATE_TRACE_BEGIN
-    const int info = bwd_dkv_unit(a, w);
-    MATE_TRACE_END(2, q, t, info)
-  });
+  Work w;
+  int queue, ticket;
+  if (!take_unit(a, 1, w, queue, ticket)) return;
+  MATE_TRACE_BEGIN
+  const int info = bwd_dkv_unit(a, w);
+  MATE_TRACE_END(2, queue, ticket, info)
 }
 
 // Adds the chunk partials of question-token rows in chunk order and stores dQ, dK, dV rows.
@@ -346,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  const dim3 grid(persistent_grid()), block(kThreads);
+  const dim3 grid(units_upper_bound(a.B, a.H, a.N)), block(kThreads);
   hipError_t e = launch_plan(a, stream);
   if (e != hipSuccess) return e;
   {

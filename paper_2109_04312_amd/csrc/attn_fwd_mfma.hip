@@ -162,11 +162,12 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a, const Work& w) {
 }
 
 __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
-  run_queues(a, 0, [&](const Work& w, int q, int t) {
-    MATE_TRACE_BEGIN
-    const int info = fwd_unit(a, w);
-    MATE_TRACE_END(0, q, t, info)
-  });
+  Work w;
+  int queue, ticket;
+  if (!take_unit(a, 0, w, queue, ticket)) return;
+  MATE_TRACE_BEGIN
+  const int info = fwd_unit(a, w);
+  MATE_TRACE_END(0, queue, ticket, info)
 }
 
 // Merges the chunk partials of question-token queries: O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
@@ -233,7 +234,7 @@ hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
   if (e != hipSuccess) return e;
   {
     ProfileScope prof(2, stream);
-    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(persistent_grid()), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(units_upper_bound(a.B, a.H, a.N)), dim3(kThreads), 0, stream, a);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;

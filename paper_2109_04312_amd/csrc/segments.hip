@@ -1,8 +1,16 @@
 // Segment builder: the per-head-kind reordering of Section 3.1 (row-order / column-order
-// traversal of the table tokens), computed as a stable sort by id plus run boundaries.
-// Integer work only.  One 1024-thread workgroup per (sequence, view); the whole sort lives in
-// LDS as a bitonic network over 64-bit keys (id << 32 | position): positions make all keys
-// distinct, so any correct sort of them IS the stable sort by id.
+// traversal of the table tokens), computed as a stable sort of the table-token positions by id
+// plus run boundaries.  Integer work only.  One 1024-thread workgroup per (sequence, view); the
+// whole sort lives in LDS.
+//
+// Sort: table-token positions are first compacted in ascending order, then reordered by a
+// least-significant-digit radix sort on their id, 8 bits per pass.  Each pass is stable (every
+// wavefront owns a contiguous block of the current order, counts its digits, and ranks equal
+// digits inside a 64-element batch in lane order with ballots), so ties keep ascending position.
+// Passes whose digit is zero for every id are skipped: ids below 65536 cost two passes.
+//
+// The kernel also prepares what the attention kernels need per (sequence, view): for every
+// 128-slot tile of the sorted order, the window of sorted slots its segments span.
 #include <hip/hip_runtime.h>
 
 #include "launch.h"
@@ -42,11 +50,17 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int* __restrict__ row_ids, const int* __restrict__ col_ids,
     const unsigned char* __restrict__ flags, int B, int N, int* __restrict__ seg) {
   constexpr int PER = P2 / kSegThreads;  // consecutive elements owned by one thread
+  constexpr int CHUNK = P2 / kSegWaves;  // consecutive elements owned by one wavefront
   static_assert(PER >= 1, "P2 must be at least the workgroup size");
-  __shared__ unsigned long long keys[P2];
+  __shared__ int ids[P2];                  // id by token position; later: segment starts (ushort)
+  __shared__ unsigned short buf_a[P2];     // current order of table-token positions
+  __shared__ unsigned short buf_b[P2];     // next order; later: segment index by slot
+  __shared__ int hist[kSegWaves][256];     // per-wavefront digit counts -> running output slots
   __shared__ int scan_tmp[kSegWaves + 1];
+  __shared__ int s_or;
 
   const int b = blockIdx.x, view = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const SegLayout lay(B, N);
   int* counts = seg + lay.counts + (size_t)b * kCountWords;
   int* global_idx = seg + lay.global_idx + (size_t)b * N;
@@ -56,101 +70,140 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   int* seg_off = vbase + lay.seg_off + (size_t)b * (N + 1);
   int* seg_of_tok = vbase + lay.seg_of_tok + (size_t)b * N;
   int2* slot_rng = reinterpret_cast<int2*>(vbase + lay.slot_rng) + (size_t)b * N;
-  const int* ids = (view == 0 ? row_ids : col_ids) + (size_t)b * N;
+  int4* tile_desc = reinterpret_cast<int4*>(vbase + lay.tile_desc) + (size_t)b * lay.tiles;
+  const int* id_src = (view == 0 ? row_ids : col_ids) + (size_t)b * N;
   const unsigned char* fl = flags + (size_t)b * N;
 
   if (b == 0 && view == 0 && tid < kHdrWords)
     seg[tid] = tid == 0 ? kMagic : tid == 1 ? B : tid == 2 ? N : 0;
+  if (tid == 0) s_or = 0;
 
-  // ---- classify: keys for table tokens, sentinel for everything else -------------------
-  int n_g = 0, n_p = 0, n_l = 0, bad = 0;
+  // ---- classify; compact the three kinds of position in ascending order -------------------
+  int n_g = 0, n_p = 0, n_l = 0, bad = 0, my_or = 0;
   unsigned char my_flag[PER];
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int i = tid * PER + e;
-    unsigned long long key = ~0ull;
-    unsigned char f = 2;
+    unsigned char f = 3;
     if (i < N) {
       f = fl[i];
       if (f > 2) { bad = 1; f = 2; }
       if (f == 0) {
-        const int id = ids[i];
+        const int id = id_src[i];
         if (id < 0) bad = 1;
-        key = ((unsigned long long)(unsigned)id << 32) | (unsigned)i;
+        ids[i] = id;
+        my_or |= id;
         ++n_l;
       } else {
         seg_of_tok[i] = -1;
         if (f == 1) ++n_g; else ++n_p;
       }
     }
-    my_flag[e] = i < N ? f : (unsigned char)3;
-    keys[i] = key;
+    my_flag[e] = f;
   }
   int G, P, L;
   int g_at = block_exclusive_scan(n_g, scan_tmp, G);
   int p_at = block_exclusive_scan(n_p, scan_tmp, P);
-  (void)block_exclusive_scan(n_l, scan_tmp, L);
+  int l_at = block_exclusive_scan(n_l, scan_tmp, L);
   const int any_bad = __syncthreads_or(bad);
-  if (view == 0) {
+  if (my_or) atomicOr(&s_or, my_or);
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int i = tid * PER + e;
+  for (int e = 0; e < PER; ++e) {
+    const int i = tid * PER + e;
+    if (my_flag[e] == 0) buf_a[l_at++] = (unsigned short)i;
+    if (view == 0) {
       if (my_flag[e] == 1) global_idx[g_at++] = i;
       if (my_flag[e] == 2) pad_idx[p_at++] = i;
     }
+  }
+  if (view == 0) {
     for (int i = G + tid; i < N; i += kSegThreads) global_idx[i] = -1;
     for (int i = P + tid; i < N; i += kSegThreads) pad_idx[i] = -1;
-    if (tid == 0) { counts[C_G] = G; counts[C_L] = L; counts[C_P] = P; counts[7] = 0; }
+    if (tid == 0) { counts[C_G] = G; counts[C_L] = L; counts[C_P] = P; }
   }
   if (tid == 0) counts[5 + view] = any_bad;
+  __syncthreads();
+  const unsigned all_bits = (unsigned)s_or;
 
-  // ---- bitonic sort of keys[0..P2) ascending ------------------------------------------
-  for (int k = 2; k <= P2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < (PER + 1) / 2; ++e) {
-        const int t = tid + e * kSegThreads;  // pair index, P2/2 pairs
-        if (PER == 1 && t >= P2 / 2) break;
-        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-        const int p = i | j;
-        const unsigned long long a = keys[i], c = keys[p];
-        const bool asc = (i & k) == 0;
-        if ((a > c) == asc) { keys[i] = c; keys[p] = a; }
+  // ---- stable LSD radix sort of buf_a[0..L) by ids[position] --------------------------------
+  unsigned short* cur = buf_a;
+  unsigned short* nxt = buf_b;
+  for (int shift = 0; shift < 32; shift += 8) {
+    if (((all_bits >> shift) & 255u) == 0) continue;  // this digit is 0 everywhere: order unchanged
+    for (int i = tid; i < kSegWaves * 256; i += kSegThreads) (&hist[0][0])[i] = 0;
+    __syncthreads();
+    const int w_lo = wave * CHUNK, w_hi = min(w_lo + CHUNK, L);
+    for (int s0 = w_lo; s0 < w_hi; s0 += 64) {
+      const int s = s0 + lane;
+      if (s < w_hi) atomicAdd(&hist[wave][((unsigned)ids[cur[s]] >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    // counts -> first output slot of (digit, wavefront): digits ascending, wavefronts ascending
+    int tot = 0;
+    if (tid < 256) {
+      for (int w = 0; w < kSegWaves; ++w) {
+        const int c = hist[w][tid];
+        hist[w][tid] = tot;
+        tot += c;
       }
     }
+    int all;
+    const int digit_base = block_exclusive_scan(tot, scan_tmp, all);
+    if (tid < 256)
+      for (int w = 0; w < kSegWaves; ++w) hist[w][tid] += digit_base;
+    __syncthreads();
+    // rank inside each 64-element batch in lane order; batches of a wavefront go in sequence
+    for (int s0 = w_lo; s0 < w_hi; s0 += 64) {
+      const int s = s0 + lane;
+      const bool valid = s < w_hi;
+      const unsigned pos = valid ? cur[s] : 0u;
+      const unsigned digit = valid ? ((unsigned)ids[pos] >> shift) & 255u : 0u;
+      unsigned long long same = __ballot(valid);
+#pragma unroll
+      for (int bit = 0; bit < 8; ++bit) {
+        const bool one = (digit >> bit) & 1u;
+        const unsigned long long m = __ballot(one);
+        same &= one ? m : ~m;
+      }
+      if (valid) {
+        const int rank = __popcll(same & ((1ull << lane) - 1ull));
+        const int base = hist[wave][digit];
+        nxt[base + rank] = (unsigned short)pos;
+        if (rank == __popcll(same) - 1) hist[wave][digit] = base + __popcll(same);
+      }
+    }
+    __syncthreads();
+    unsigned short* t = cur; cur = nxt; nxt = t;
   }
-  __syncthreads();
 
-  // ---- run boundaries -> segment index per slot ----------------------------------------
-  unsigned long long mine[PER];
-  int head[PER];
+  // ---- run boundaries -> segment index per slot ----------------------------------------------
+  int head[PER], my_pos[PER];
   int n_head = 0;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int s = tid * PER + e;
-    mine[e] = keys[s];
     head[e] = 0;
+    my_pos[e] = 0;
     if (s < L) {
-      head[e] = (s == 0) || ((keys[s - 1] >> 32) != (mine[e] >> 32));
+      my_pos[e] = cur[s];
+      head[e] = (s == 0) || (ids[cur[s - 1]] != ids[my_pos[e]]);
       n_head += head[e];
     }
   }
   int S;
   int seg_idx = block_exclusive_scan(n_head, scan_tmp, S) - 1;  // ends with a barrier
-  // keys[] is dead now; reuse its bytes as two int arrays.
-  int* seg_of_slot = reinterpret_cast<int*>(keys);       // [P2]
-  int* seg_start = seg_of_slot + P2;                      // [P2], entry S (== L) is implied
+  // ids[] and the spare order buffer are dead now: reuse them
+  unsigned short* seg_start = reinterpret_cast<unsigned short*>(ids);  // [P2], entry S (== L) implied
+  unsigned short* seg_of_slot = nxt;                                    // [P2]
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int s = tid * PER + e;
     if (s < L) {
       seg_idx += head[e];
-      const int pos = (int)(unsigned)(mine[e] & 0xffffffffu);
-      perm[s] = pos;
-      seg_of_tok[pos] = seg_idx;
-      seg_of_slot[s] = seg_idx;
-      if (head[e]) { seg_start[seg_idx] = s; seg_off[seg_idx] = s; }
+      perm[s] = my_pos[e];
+      seg_of_tok[my_pos[e]] = seg_idx;
+      seg_of_slot[s] = (unsigned short)seg_idx;
+      if (head[e]) { seg_start[seg_idx] = (unsigned short)s; seg_off[seg_idx] = s; }
     } else if (s < N) {
       perm[s] = -1;
     }
@@ -158,19 +211,31 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   if (tid == 0) { seg_off[S] = L; counts[C_SROW + view] = S; }
   for (int i = S + 1 + tid; i <= N; i += kSegThreads) seg_off[i] = -1;
   __syncthreads();
+  auto seg_lo = [&](int s) { return (int)seg_start[seg_of_slot[s]]; };
+  auto seg_hi = [&](int s) {
+    const int g = seg_of_slot[s];
+    return g + 1 < S ? (int)seg_start[g + 1] : L;
+  };
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int s = tid * PER + e;
-    if (s < N) {
-      int2 r = make_int2(0, 0);
-      if (s < L) {
-        const int g = seg_of_slot[s];
-        r.x = seg_start[g];
-        r.y = (g + 1 < S) ? seg_start[g + 1] : L;
-      }
-      slot_rng[s] = r;
-    }
+    if (s < N) slot_rng[s] = s < L ? make_int2(seg_lo(s), seg_hi(s)) : make_int2(0, 0);
   }
+
+  // ---- tiles of 128 sorted slots: the slot window spanned by the segments a tile touches ------
+  const int n_tiles = (L + kTileSlots - 1) / kTileSlots;
+  int my_len = 0;
+  if (tid < n_tiles) {
+    const int t0 = tid * kTileSlots, lo = seg_lo(t0), hi = seg_hi(min(t0 + kTileSlots, L) - 1);
+    my_len = hi - lo;
+    tile_desc[tid] = make_int4(t0, lo, hi, 0);
+  } else if (tid < lay.tiles) {
+    tile_desc[tid] = make_int4(-1, 0, 0, 0);  // no such tile
+  }
+  // streamed 64-slot tiles of all units of this view, for the scheduler's "which kind is longer"
+  int my_cost = (my_len + 63) / 64, cost;
+  (void)block_exclusive_scan(my_cost, scan_tmp, cost);
+  if (tid == 0) counts[C_COST_ROW + view] = cost;
 }
 
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,

@@ -13,9 +13,12 @@
 //           results, merged by a finalize kernel.  n_gt * n_chunks <= UG = ceil(N / 128).
 //   pad     n_pt = ceil(P / 128) pad owners (zero fill)
 // G, L, P live on the device, so a small plan kernel counts the units and lays them out in
-// eight work queues (one per XCD, so that the units of one (sequence, head) share an L2),
-// longest kind of unit first; persistent workgroups pull tickets from the queue of their own
-// XCD and steal from the others when it runs dry.
+// eight work queues, one per XCD.  A queue lists whole (sequence, head) pairs -- those of the
+// head kind with more work first -- and each pair's units in the order local tiles (ascending
+// slot), question-token chunks, pad tiles.  Workgroups of an XCD therefore work on one or two
+// pairs at a time, whose K / V (or Q / dO) fit that XCD's L2 and are fetched from HBM once for
+// all of the pair's units; every workgroup draws one ticket from the queue of its own XCD and
+// steals from the others when that runs dry.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -52,17 +55,17 @@ __device__ inline GlobalSplit global_split(int G, int L, int N) {
 }
 
 // ---- plan buffer (ints, in the caller's workspace) -------------------------------------------
-//   [0, 16)            ticket counters: [kernel slot 0..1][queue 0..7]
-//   [24]               first_view: the view whose table-token units stream more tiles
-//   [32 + 8 q + band]  number of units of queue q in bands 0..band (inclusive prefix), band < 4:
-//                      0 local units of first_view heads, 1 local units of the other heads,
-//                      2 question-token units, 3 pad units
-//   [96 + ((4 q + band) (nq + 1)) + j]  exclusive prefix over the queue's (b,h) pairs
-//                      bh = q + 8 j, j < nq = ceil(B H / 8), of their units in that band
-constexpr int kPlanCounters = 0, kPlanFirstView = 24, kPlanCum = 32, kPlanPref = 96;
+//   [0, 16)                       ticket counters: [kernel slot 0..1][queue 0..7]
+//   [24]                          first_view: the view whose table-token units stream more tiles
+//   [32 + q]                      tickets of queue q
+//   [64 + q (nq + 1) + j]         exclusive prefix of the units of the queue's pairs, in queue
+//                                 order, j <= nq = ceil(B H / 8)
+//   [64 + 8 (nq + 1) + q nq + j]  the pairs of queue q in queue order, as b * H + h
+constexpr int kPlanCounters = 0, kPlanFirstView = 24, kPlanTotal = 32, kPlanPref = 64;
 __host__ __device__ inline int plan_nq(int BH) { return (BH + 7) >> 3; }
+__host__ __device__ inline int plan_list(int BH) { return kPlanPref + 8 * (plan_nq(BH) + 1); }
 __host__ __device__ inline size_t plan_words(int BH) {
-  return (size_t)kPlanPref + 32 * (size_t)(plan_nq(BH) + 1);
+  return (size_t)plan_list(BH) + 8 * (size_t)plan_nq(BH);
 }
 
 enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
@@ -92,18 +95,16 @@ __device__ inline UnitPlan plan_base(const AttnArgs& a, int b) {
   u.t_begin = u.t_end = 0;
   return u;
 }
-// Table-token owner number `tile` of (b, view).
-__device__ inline UnitPlan plan_local(const AttnArgs& a, int b, int view, int tile) {
+// Table-token owner described by `desc` = (first slot, streamed window lo, hi) of (b, view).
+__device__ inline UnitPlan plan_local(const AttnArgs& a, int b, int view, int4 desc) {
   UnitPlan u = plan_base(a, b);
-  const int N = a.N;
   u.kind = UNIT_LOCAL;
-  u.t0 = tile * BM;
-  u.own_list = a.seg.perm[view] + (size_t)b * N;
+  u.t0 = desc.x;
+  u.own_list = a.seg.perm[view] + (size_t)b * a.N;
   u.own_count = u.L;
   u.str_list = u.own_list;
-  const int2* rng = a.seg.slot_rng[view] + (size_t)b * N;
-  u.s_lo = rng[u.t0].x;
-  u.s_hi = rng[min(u.t0 + BM, u.L) - 1].y;
+  u.s_lo = desc.y;
+  u.s_hi = desc.z;
   u.t_end = u.n_t0 + (u.s_hi - u.s_lo + BN - 1) / BN;
   return u;
 }
@@ -160,59 +161,64 @@ struct Work {
 
 __device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7; }  // XCC_ID[3:0]
 
-// Unit number `t` of queue `q` -> which (b,h), which unit.  All inputs wave-uniform.
+// Ticket `t` of queue `q` -> which (b,h), which unit.  All inputs wave-uniform.
 __device__ inline Work decode_ticket(const AttnArgs& a, int q, int t) {
   const int BH = a.B * a.H, nq = plan_nq(BH);
-  const int* cum = a.plan + kPlanCum + 8 * q;
-  int band = 0, r = t;
-  while (band < 3 && t >= cum[band]) ++band;
-  if (band) r = t - cum[band - 1];
-  const int* pref = a.plan + kPlanPref + (4 * q + band) * (nq + 1);
-  int lo = 0, hi = nq;  // largest j with pref[j] <= r
+  const int* pref = a.plan + kPlanPref + q * (nq + 1);
+  int lo = 0, hi = nq;  // largest j with pref[j] <= t
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (pref[mid] <= r) lo = mid; else hi = mid;
+    if (pref[mid] <= t) lo = mid; else hi = mid;
   }
   Work w;
-  w.bh = q + 8 * lo;
-  const int unit = r - pref[lo];
-  const int b = w.bh / a.H, h = w.bh % a.H;
-  w.view = a.head_kind[h];
-  if (band < 2) w.u = plan_local(a, b, w.view, unit);
-  else if (band == 2) w.u = plan_global(a, b, unit);
-  else w.u = plan_pad(a, b, unit);
+  w.bh = a.plan[plan_list(BH) + q * nq + lo];
+  int unit = t - pref[lo];
+  const int b = w.bh / a.H;
+  w.view = a.head_kind[w.bh % a.H];
+  const int L = a.seg.counts[(size_t)b * kCountWords + C_L];
+  const int n_lt = (L + BM - 1) / BM;
+  if (unit < n_lt) {
+    w.u = plan_local(a, b, w.view, a.seg.tile_desc[w.view][(size_t)b * a.seg.tiles + unit]);
+    return w;
+  }
+  unit -= n_lt;
+  const int G = a.seg.counts[(size_t)b * kCountWords + C_G];
+  const GlobalSplit s = global_split(G, L, a.N);
+  const int n_gu = s.n_gt * s.n_chunks;
+  w.u = unit < n_gu ? plan_global(a, b, unit) : plan_pad(a, b, unit - n_gu);
   return w;
 }
 
-// Persistent workgroup: pull tickets from the queue of this workgroup's XCD, then from the
-// others; `body(work, queue, ticket)` must leave LDS reusable for the next unit when it returns.
-template <typename Body>
-__device__ inline void run_queues(const AttnArgs& a, int kernel_slot, Body body) {
+// One unit per workgroup: draw a ticket from the queue of this workgroup's XCD, or, if that
+// queue is exhausted, from the others in turn.  The host launches as many workgroups as there
+// can be units (upper bound from B, H, N); the surplus finds every queue empty and exits.
+// (A persistent loop over tickets was tried and lost: with the unit body inside a loop the
+// compiler runs out of scalar registers and moves the wave-uniform bookkeeping into vector
+// registers and vector ALU work; the hardware's workgroup dispatcher is the faster loop.)
+// Returns false if there is nothing left to do.
+__device__ inline bool take_unit(const AttnArgs& a, int kernel_slot, Work& w, int& queue, int& ticket) {
   __shared__ int s_ticket, s_queue;
-  int* counters = a.plan + kPlanCounters + 8 * kernel_slot;
-  int q = xcc_id(), tried = 0;
-  for (;;) {
-    __syncthreads();  // the previous unit is completely done with LDS, s_ticket and s_queue
-    if (threadIdx.x == 0) {
-      int t = -1;
-      while (tried < 8) {
-        t = atomicAdd(&counters[q], 1);
-        if (t < a.plan[kPlanCum + 8 * q + 3]) break;
-        q = (q + 1) & 7;
-        ++tried;
-        t = -1;
-      }
-      s_ticket = t;
-      s_queue = q;
+  if (threadIdx.x == 0) {
+    int* counters = a.plan + kPlanCounters + 8 * kernel_slot;
+    int q = xcc_id(), t = -1;
+    for (int tried = 0; tried < 8; ++tried, q = (q + 1) & 7) {
+      if (counters[q] >= a.plan[kPlanTotal + q]) continue;  // looks exhausted: do not bump it
+      t = atomicAdd(&counters[q], 1);
+      if (t < a.plan[kPlanTotal + q]) break;
+      t = -1;
     }
-    __syncthreads();
-    // wave-uniform values: keep the whole unit description in scalar registers
-    const int t = __builtin_amdgcn_readfirstlane(s_ticket);
-    const int tq = __builtin_amdgcn_readfirstlane(s_queue);
-    if (t < 0) return;
-    body(decode_ticket(a, tq, t), tq, t);
+    s_ticket = t;
+    s_queue = q;
   }
+  __syncthreads();
+  // wave-uniform values: keep the whole unit description in scalar registers
+  ticket = __builtin_amdgcn_readfirstlane(s_ticket);
+  queue = __builtin_amdgcn_readfirstlane(s_queue);
+  if (ticket < 0) return false;
+  w = decode_ticket(a, queue, ticket);
+  return true;
 }
+inline int units_upper_bound(int B, int H, int N) { return B * H * (2 * owner_slots(N) + 1); }
 
 // Streamed tile t of a unit: which index list, first slot, last valid slot.
 __device__ inline void tile_source(const UnitPlan& u, const int* global_idx, int t,
