@@ -57,7 +57,6 @@ hipError_t launch_bwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
 // Counts the units of every (b,h), lays out the eight work queues and zeroes their ticket
 // counters; must precede the MFMA kernels of a call on the same stream.
 hipError_t launch_plan(const AttnArgs& a, hipStream_t stream);
-int persistent_grid();  // workgroups to launch: 2 per compute unit of the current device
 
 // bf16 MFMA kernels.
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream);

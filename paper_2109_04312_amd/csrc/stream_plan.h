@@ -13,12 +13,9 @@
 //           results, merged by a finalize kernel.  n_gt * n_chunks <= UG = ceil(N / 128).
 //   pad     n_pt = ceil(P / 128) pad owners (zero fill)
 // G, L, P live on the device, so a small plan kernel counts the units and lays them out in
-// eight work queues, one per XCD.  A queue lists whole (sequence, head) pairs -- those of the
-// head kind with more work first -- and each pair's units in the order local tiles (ascending
-// slot), question-token chunks, pad tiles.  Workgroups of an XCD therefore work on one or two
-// pairs at a time, whose K / V (or Q / dO) fit that XCD's L2 and are fetched from HBM once for
-// all of the pair's units; every workgroup draws one ticket from the queue of its own XCD and
-// steals from the others when that runs dry.
+// eight work queues, one per XCD (queue q holds the (sequence, head) pairs b H + h = q mod 8, so
+// that the units of one pair share an L2).  Every workgroup draws one ticket from the queue of
+// its own XCD and steals from the others when that runs dry.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -55,17 +52,18 @@ __device__ inline GlobalSplit global_split(int G, int L, int N) {
 }
 
 // ---- plan buffer (ints, in the caller's workspace) -------------------------------------------
-//   [0, 16)                       ticket counters: [kernel slot 0..1][queue 0..7]
-//   [24]                          first_view: the view whose table-token units stream more tiles
-//   [32 + q]                      tickets of queue q
-//   [64 + q (nq + 1) + j]         exclusive prefix of the units of the queue's pairs, in queue
-//                                 order, j <= nq = ceil(B H / 8)
-//   [64 + 8 (nq + 1) + q nq + j]  the pairs of queue q in queue order, as b * H + h
-constexpr int kPlanCounters = 0, kPlanFirstView = 24, kPlanTotal = 32, kPlanPref = 64;
+//   [0, 16)    ticket counters: [kernel slot 0..1][queue 0..7]
+//   [32 + q]   tickets of queue q
+//   [40 + q]   (sequence, head) pairs of queue q: bh = q + 8 j, j < pairs
+//   [48 + q]   the largest number of table-token tiles of one of those pairs
+//   [64 + (2 q + k)(nq + 1) + j]  k = 0: exclusive prefix over the queue's pairs of their pad
+//              units, k = 1: of their question-token units; nq = ceil(B H / 8)
+// Ticket order of a queue: table-token tile 0 of every pair, tile 1 of every pair, ... (tickets
+// of pairs that have fewer tiles are empty), then the pad units, then the question-token units.
+constexpr int kPlanCounters = 0, kPlanTotal = 32, kPlanPairs = 40, kPlanMost = 48, kPlanPref = 64;
 __host__ __device__ inline int plan_nq(int BH) { return (BH + 7) >> 3; }
-__host__ __device__ inline int plan_list(int BH) { return kPlanPref + 8 * (plan_nq(BH) + 1); }
 __host__ __device__ inline size_t plan_words(int BH) {
-  return (size_t)plan_list(BH) + 8 * (size_t)plan_nq(BH);
+  return (size_t)kPlanPref + 16 * (size_t)(plan_nq(BH) + 1);
 }
 
 enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
@@ -161,31 +159,38 @@ struct Work {
 
 __device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7; }  // XCC_ID[3:0]
 
-// Ticket `t` of queue `q` -> which (b,h), which unit.  All inputs wave-uniform.
+// Ticket `t` of queue `q` -> which (b,h), which unit (kind UNIT_NONE: an empty ticket).  All
+// inputs wave-uniform.
 __device__ inline Work decode_ticket(const AttnArgs& a, int q, int t) {
-  const int BH = a.B * a.H, nq = plan_nq(BH);
-  const int* pref = a.plan + kPlanPref + q * (nq + 1);
+  const int nq = plan_nq(a.B * a.H);
+  const int pairs = a.plan[kPlanPairs + q], most = a.plan[kPlanMost + q];
+  Work w;
+  if (t < pairs * most) {
+    const int j = t % pairs, k = t / pairs;
+    w.bh = q + 8 * j;
+    const int b = w.bh / a.H;
+    w.view = a.head_kind[w.bh % a.H];
+    const int4 desc = a.seg.tile_desc[w.view][(size_t)b * a.seg.tiles + k];
+    if (desc.x < 0) w.u.kind = UNIT_NONE;
+    else w.u = plan_local(a, b, w.view, desc);
+    return w;
+  }
+  t -= pairs * most;
+  const int* pref = a.plan + kPlanPref + 2 * q * (nq + 1);
+  const int is_global = t >= pref[nq];
+  if (is_global) {
+    t -= pref[nq];
+    pref += nq + 1;
+  }
   int lo = 0, hi = nq;  // largest j with pref[j] <= t
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
     if (pref[mid] <= t) lo = mid; else hi = mid;
   }
-  Work w;
-  w.bh = a.plan[plan_list(BH) + q * nq + lo];
-  int unit = t - pref[lo];
+  w.bh = q + 8 * lo;
   const int b = w.bh / a.H;
   w.view = a.head_kind[w.bh % a.H];
-  const int L = a.seg.counts[(size_t)b * kCountWords + C_L];
-  const int n_lt = (L + BM - 1) / BM;
-  if (unit < n_lt) {
-    w.u = plan_local(a, b, w.view, a.seg.tile_desc[w.view][(size_t)b * a.seg.tiles + unit]);
-    return w;
-  }
-  unit -= n_lt;
-  const int G = a.seg.counts[(size_t)b * kCountWords + C_G];
-  const GlobalSplit s = global_split(G, L, a.N);
-  const int n_gu = s.n_gt * s.n_chunks;
-  w.u = unit < n_gu ? plan_global(a, b, unit) : plan_pad(a, b, unit - n_gu);
+  w.u = is_global ? plan_global(a, b, t - pref[lo]) : plan_pad(a, b, t - pref[lo]);
   return w;
 }
 
@@ -216,7 +221,7 @@ __device__ inline bool take_unit(const AttnArgs& a, int kernel_slot, Work& w, in
   queue = __builtin_amdgcn_readfirstlane(s_queue);
   if (ticket < 0) return false;
   w = decode_ticket(a, queue, ticket);
-  return true;
+  return w.u.kind != UNIT_NONE;
 }
 inline int units_upper_bound(int B, int H, int N) { return B * H * (2 * owner_slots(N) + 1); }
 
