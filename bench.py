@@ -28,8 +28,13 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 D = 64
 # HBM bytes per launch on the headline workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (summaries and the scaling against a copy kernel are under profiles/); None = not measured
-TRAFFIC = {}
+# (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0, the factors a plain copy of known size gives;
+# summaries under profiles/); a kernel or workload that is not listed reports null
+TRAFFIC = {"cfg4_B2_N8192_H16": {
+    "fwd_mfma_kernel": {"fetch_bytes": 64874 * 2048, "write_bytes": 52821 * 1024},
+    "bwd_dq_mfma_kernel": {"fetch_bytes": 92995 * 2048, "write_bytes": 52598 * 1024},
+    "bwd_dkv_mfma_kernel": {"fetch_bytes": 82754 * 2048, "write_bytes": 96362 * 1024},
+}}
 
 
 def useful_pairs_per_view(st):
@@ -78,6 +83,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration (default: headline 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 256 MiB device copy three times (to scale the "
+                         "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -86,6 +94,16 @@ def main():
 
     import torch
     from paper_2109_04312_amd import mate, synth
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_each_way": src.numel() * 4}))
+        return
 
     w = synth.make_config(args.config)
     B, H, N, _ = w.shape
@@ -163,6 +181,12 @@ def main():
     dom = max(cand, key=lambda n: cand[n][1])
     ach = cand[dom][0] / cand[dom][1] / 1e12
     t_attn = ms_per_step * 1e-3 - t_build
+    traffic = TRAFFIC.get(w.name, {}).get(dom)
+    traffic_detail = None
+    if traffic is not None:
+        traffic_detail = dict(traffic, unit="HBM bytes per launch",
+                              source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy")
+        traffic = traffic["fetch_bytes"] + traffic["write_bytes"]
 
     res = {
         "metric": "MATE attn fwd+bwd tokens/s & useful-pair TFLOP/s, seq 8192, 16 heads, 1 GPU",
@@ -179,7 +203,7 @@ def main():
         "ms_per_step_event_pass": ms_per_step_pass2,
         "flop_convention": "fwd 4*D, bwd 10*D flop per useful (query,key) pair; exp not counted",
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC.get(dom),
+                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "algorithmic_flop_per_launch": cand[dom][0],
                      "avg_launch_us": cand[dom][1] * 1e6},
         "segment_builder": {"us": t_build * 1e6, "keys_per_s": 2 * tokens / t_build,
