@@ -2,7 +2,6 @@
 // stream.  No allocation, no global state.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -28,7 +27,6 @@ size_t delta_bytes(int B, int H, int N) { return align16((size_t)B * H * N * siz
 // partial results of chunked question-token owners (bf16 MFMA path only)
 size_t part_bytes(int B, int H, int N) { return (size_t)B * H * part_words_per_bh(N) * sizeof(float); }
 size_t stat_bytes(int B, int H, int N) { return (size_t)B * H * stat_words_per_bh(N) * sizeof(float); }
-size_t plan_bytes(int B, int H) { return align16(plan_words(B * H) * sizeof(int)); }
 
 mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kind, int B, int H,
                       int N, int D, mate_dtype t, float scale) {
@@ -46,9 +44,6 @@ mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kin
   a.H = H;
   a.N = N;
   a.scale = scale;
-#ifdef MATE_TRACE
-  if (const char* e = std::getenv("MATE_TRACE_PTR")) a.trace = reinterpret_cast<long long*>(std::strtoull(e, nullptr, 0));
-#endif
   return MATE_OK;
 }
 
@@ -65,8 +60,8 @@ size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bw
   if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS || D != MATE_HEAD_DIM) return 0;
   if (t == MATE_F32) return for_bwd ? delta_bytes(B, H, N) : 0;
   if (t != MATE_BF16) return 0;
-  return plan_bytes(B, H) + (for_bwd ? delta_bytes(B, H, N) + 3 * part_bytes(B, H, N)
-                                    : part_bytes(B, H, N) + stat_bytes(B, H, N));
+  return for_bwd ? delta_bytes(B, H, N) + 3 * part_bytes(B, H, N)
+                 : part_bytes(B, H, N) + stat_bytes(B, H, N);
 }
 
 mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
@@ -128,8 +123,6 @@ mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const voi
   a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse;
   if (t == MATE_BF16) {
     char* p = static_cast<char*>(workspace);
-    a.plan = reinterpret_cast<int*>(p);
-    p += plan_bytes(B, H);
     a.part[0] = reinterpret_cast<float*>(p);
     a.part_ml = reinterpret_cast<float*>(p + part_bytes(B, H, N));
   }
@@ -154,11 +147,7 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.delta = static_cast<float*>(workspace);
   if (t == MATE_BF16) {
-    char* p = static_cast<char*>(workspace);
-    a.plan = reinterpret_cast<int*>(p);
-    p += plan_bytes(B, H);
-    a.delta = reinterpret_cast<float*>(p);
-    p += delta_bytes(B, H, N);
+    char* p = static_cast<char*>(workspace) + delta_bytes(B, H, N);
     for (int i = 0; i < 3; ++i) a.part[i] = reinterpret_cast<float*>(p + i * part_bytes(B, H, N));
   }
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -31,7 +31,7 @@ namespace {
 constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
 constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, lse[64], delta[64]
 
-__device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a, const Work& w) {
+__device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kDqStage];
   __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int q_tok[BM];
@@ -54,7 +54,7 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a, const Work& w) {
 
   if (u.kind == UNIT_PAD) {
     zero_pad_rows(dQ, u, tid);
-    return unit_info(u);
+    return;
   }
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
   if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
@@ -142,25 +142,22 @@ __device__ __forceinline__ int bwd_dq_unit(const AttnArgs& a, const Work& w) {
   if (u.part >= 0) {
     const size_t slot = (size_t)w.bh * owner_slots(N) + u.part;
     store_partial(dq_acc, a.scale, a.part[0] + slot * BM * kD, wave, lane);
-    return unit_info(u);
+    return;
   }
   store_owned_rows(dq_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dQ, q_tok, wave, lane);
-  return unit_info(u);
+  return;
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
   Work w;
-  int queue, ticket;
-  if (!take_unit(a, 0, w, queue, ticket)) return;
-  MATE_TRACE_BEGIN
-  const int info = bwd_dq_unit(a, w);
-  MATE_TRACE_END(1, queue, ticket, info)
+  if (!take_unit(a, w)) return;
+  bwd_dq_unit(a, w);
 }
 
 // ======================================================================================
 // dK, dV
 // ======================================================================================
-__device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a, const Work& w) {
+__device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kDkvStage];
   __shared__ int idx_ring[4][kIdxSlots][BN];
   __shared__ int k_tok[BM];
@@ -184,7 +181,7 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   if (u.kind == UNIT_PAD) {
     zero_pad_rows(dK, u, tid);
     zero_pad_rows(dV, u, tid);
-    return unit_info(u);
+    return;
   }
   // `me` is this lane's key; its window is the set of query slots that see it
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
@@ -285,20 +282,17 @@ __device__ __forceinline__ int bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     const size_t slot = (size_t)w.bh * owner_slots(N) + u.part;
     store_partial(dk_acc, a.scale, a.part[1] + slot * BM * kD, wave, lane);
     store_partial(dv_acc, 1.f, a.part[2] + slot * BM * kD, wave, lane);
-    return unit_info(u);
+    return;
   }
   store_owned_rows(dk_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dK, k_tok, wave, lane);
   store_owned_rows(dv_acc, 1.f, reinterpret_cast<unsigned short*>(lds), dV, k_tok, wave, lane);
-  return unit_info(u);
+  return;
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
   Work w;
-  int queue, ticket;
-  if (!take_unit(a, 1, w, queue, ticket)) return;
-  MATE_TRACE_BEGIN
-  const int info = bwd_dkv_unit(a, w);
-  MATE_TRACE_END(2, queue, ticket, info)
+  if (!take_unit(a, w)) return;
+  bwd_dkv_unit(a, w);
 }
 
 // Adds the chunk partials of question-token rows in chunk order and stores dQ, dK, dV rows.
@@ -348,9 +342,8 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  const dim3 grid(units_upper_bound(a.B, a.H, a.N)), block(kThreads);
-  hipError_t e = launch_plan(a, stream);
-  if (e != hipSuccess) return e;
+  const dim3 grid(unit_grid(a.B, a.H, a.N)), block(kThreads);
+  hipError_t e;
   {
     ProfileScope prof(3, stream);
     hipLaunchKernelGGL(bwd_dq_mfma_kernel, grid, block, 0, stream, a);

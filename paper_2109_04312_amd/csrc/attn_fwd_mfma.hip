@@ -25,7 +25,7 @@ namespace {
 
 constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
 
-__device__ __forceinline__ int fwd_unit(const AttnArgs& a, const Work& w) {
+__device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
   __shared__ int idx_ring[4][kIdxSlots][BN];  // [wavefront][tile & 7][row] token positions
   __shared__ int q_tok[BM];
@@ -48,7 +48,7 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a, const Work& w) {
   if (u.kind == UNIT_PAD) {  // pad positions: O = 0, LSE = 0
     zero_pad_rows(O, u, tid);
     if (tid < BM && u.t0 + tid < u.own_count) LSE[u.own_list[u.t0 + tid]] = 0.f;
-    return unit_info(u);
+    return;
   }
 
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
@@ -154,20 +154,16 @@ __device__ __forceinline__ int fwd_unit(const AttnArgs& a, const Work& w) {
     if (hl == 0)
       *reinterpret_cast<float2*>(a.part_ml + (slot * BM + wave * 32 + m) * 2) =
           make_float2(m_run == -INFINITY ? m_run : m_run * sc, l_tot);
-    return unit_info(u);
+    return;
   }
   if (hl == 0 && me.valid) LSE[me.pos] = (m_run * sc + __builtin_amdgcn_logf(l_tot)) * kLn2;
   store_owned_rows(o_acc, 1.f / l_tot, reinterpret_cast<unsigned short*>(lds), O, q_tok, wave, lane);
-  return unit_info(u);
 }
 
 __global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
   Work w;
-  int queue, ticket;
-  if (!take_unit(a, 0, w, queue, ticket)) return;
-  MATE_TRACE_BEGIN
-  const int info = fwd_unit(a, w);
-  MATE_TRACE_END(0, queue, ticket, info)
+  if (!take_unit(a, w)) return;
+  fwd_unit(a, w);
 }
 
 // Merges the chunk partials of question-token queries: O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
@@ -230,13 +226,11 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  hipError_t e = launch_plan(a, stream);
-  if (e != hipSuccess) return e;
   {
     ProfileScope prof(2, stream);
-    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(units_upper_bound(a.B, a.H, a.N)), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(unit_grid(a.B, a.H, a.N)), dim3(kThreads), 0, stream, a);
   }
-  e = hipGetLastError();
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // partials exist only while question tokens fill at most half the owner slots; a few
   // workgroups per (b,h) stride over however many question tokens there are

@@ -16,8 +16,6 @@ struct AttnArgs {
   float* part[3];           // partial results of chunked question-token owners, per (b,h):
                             //   forward: [0] unnormalised O;  backward: dQ, dK, dV
   float* part_ml;           // forward: running max (log2 domain) and sum per partial row
-  int* plan;                // unit counts, work-queue layout and ticket counters (see stream_plan.h)
-  long long* trace;         // per-workgroup timeline records; only read by MATE_TRACE builds
   SegTables seg;
   unsigned char head_kind[256];
   int B, H, N;
@@ -53,10 +51,6 @@ hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
 // They serve dtype f32 and are the fallback-free reference-quality path for it.
 hipError_t launch_fwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
 hipError_t launch_bwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
-
-// Counts the units of every (b,h), lays out the eight work queues and zeroes their ticket
-// counters; must precede the MFMA kernels of a call on the same stream.
-hipError_t launch_plan(const AttnArgs& a, hipStream_t stream);
 
 // bf16 MFMA kernels.
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream);

@@ -9,8 +9,10 @@
 // digits inside a 64-element batch in lane order with ballots), so ties keep ascending position.
 // Passes whose digit is zero for every id are skipped: ids below 65536 cost two passes.
 //
-// The kernel also prepares what the attention kernels need per (sequence, view): for every
-// 128-slot tile of the sorted order, the window of sorted slots its segments span.
+// The kernel also lists the work units of the attention kernels per (sequence, view): for every
+// 128-slot tile of the sorted order the window of sorted slots its segments span, then the pad
+// tiles, and per sequence the chunks of the question-token owners.  The attention kernels map
+// a workgroup index to one of these records with arithmetic alone.
 #include <hip/hip_runtime.h>
 
 #include "launch.h"
@@ -70,7 +72,8 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   int* seg_off = vbase + lay.seg_off + (size_t)b * (N + 1);
   int* seg_of_tok = vbase + lay.seg_of_tok + (size_t)b * N;
   int2* slot_rng = reinterpret_cast<int2*>(vbase + lay.slot_rng) + (size_t)b * N;
-  int4* tile_desc = reinterpret_cast<int4*>(vbase + lay.tile_desc) + (size_t)b * lay.tiles;
+  int4* unit = reinterpret_cast<int4*>(vbase + lay.unit) + (size_t)b * (lay.tiles + 2) * 2;
+  int4* gunit = reinterpret_cast<int4*>(seg + lay.gunit) + (size_t)b * lay.tiles * 2;
   const int* id_src = (view == 0 ? row_ids : col_ids) + (size_t)b * N;
   const unsigned char* fl = flags + (size_t)b * N;
 
@@ -222,20 +225,37 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     if (s < N) slot_rng[s] = s < L ? make_int2(seg_lo(s), seg_hi(s)) : make_int2(0, 0);
   }
 
-  // ---- tiles of 128 sorted slots: the slot window spanned by the segments a tile touches ------
-  const int n_tiles = (L + kTileSlots - 1) / kTileSlots;
-  int my_len = 0;
-  if (tid < n_tiles) {
-    const int t0 = tid * kTileSlots, lo = seg_lo(t0), hi = seg_hi(min(t0 + kTileSlots, L) - 1);
-    my_len = hi - lo;
-    tile_desc[tid] = make_int4(t0, lo, hi, 0);
-  } else if (tid < lay.tiles) {
-    tile_desc[tid] = make_int4(-1, 0, 0, 0);  // no such tile
+  // ---- work units of the attention kernels -------------------------------------------------
+  // table-token owners: 128 sorted slots each, streaming the question tokens and then the slot
+  // window spanned by the segments those slots touch; pad owners after them
+  const int n_lt = (L + kTileSlots - 1) / kTileSlots, n_pt = (P + kTileSlots - 1) / kTileSlots;
+  const int n_t0 = (G + BN - 1) / BN;
+  if (tid < lay.tiles + 2) {
+    int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
+    if (tid < n_lt) {
+      const int t0 = tid * kTileSlots, lo = seg_lo(t0), hi = seg_hi(min(t0 + kTileSlots, L) - 1);
+      r0 = make_int4(UNIT_LOCAL, t0, lo, hi);
+      r1.y = n_t0 + (hi - lo + BN - 1) / BN;
+    } else if (tid < n_lt + n_pt) {
+      r0 = make_int4(UNIT_PAD, (tid - n_lt) * kTileSlots, 0, 0);
+    }
+    unit[2 * tid] = r0;
+    unit[2 * tid + 1] = r1;
   }
-  // streamed 64-slot tiles of all units of this view, for the scheduler's "which kind is longer"
-  int my_cost = (my_len + 63) / 64, cost;
-  (void)block_exclusive_scan(my_cost, scan_tmp, cost);
-  if (tid == 0) counts[C_COST_ROW + view] = cost;
+  // question-token owners (the same for both views; written by the row view's workgroup)
+  if (view == 0 && tid < lay.tiles) {
+    const GlobalSplit gs = global_split(G, L, N);
+    int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
+    if (tid < gs.n_gt * gs.n_chunks) {
+      const int gt = tid / gs.n_chunks, c = tid % gs.n_chunks;
+      r0 = make_int4(UNIT_GLOBAL, gt * BM, 0, L);
+      r1.x = c * gs.per;
+      r1.y = min(gs.n_st, r1.x + gs.per);
+      if (gs.n_chunks > 1) r1.z = tid;
+    }
+    gunit[2 * tid] = r0;
+    gunit[2 * tid + 1] = r1;
+  }
 }
 
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,

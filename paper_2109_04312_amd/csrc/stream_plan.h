@@ -5,17 +5,19 @@
 // are symmetric: an owned table token meets the question tokens plus the table tokens of its
 // own row / column segment; an owned question token meets every non-pad token.
 //
-// Units of one (sequence, head):
-//   local   n_lt = ceil(L / 128) table-token owners, 128 consecutive slots of the head kind's
-//           sorted order
+// Units of one (sequence, head) -- listed by the segment builder, see seg_layout.h:
+//   local   ceil(L / 128) table-token owners, 128 consecutive slots of the head kind's sorted
+//           order
+//   pad     ceil(P / 128) pad owners (zero fill)
 //   global  question-token owners.  Their streamed side is the whole sequence, so it is cut into
-//           chunks of >= kMinChunkTiles tiles that run as separate units and leave partial
-//           results, merged by a finalize kernel.  n_gt * n_chunks <= UG = ceil(N / 128).
-//   pad     n_pt = ceil(P / 128) pad owners (zero fill)
-// G, L, P live on the device, so a small plan kernel counts the units and lays them out in
-// eight work queues, one per XCD (queue q holds the (sequence, head) pairs b H + h = q mod 8, so
-// that the units of one pair share an L2).  Every workgroup draws one ticket from the queue of
-// its own XCD and steals from the others when that runs dry.
+//           chunks that run as separate units and leave partial results, merged by a finalize
+//           kernel.
+// Workgroup -> unit is arithmetic on the workgroup index plus one record read: no counters, no
+// atomics, no dependent loads.  Workgroup i serves queue i mod 8 (consecutive workgroups go to
+// consecutive XCDs, so a queue stays on one XCD and the units of one (sequence, head) pair
+// share an L2); queue q holds the pairs b H + h = q mod 8.  Order inside a queue: table-token
+// (then pad) tile 0 of every pair, tile 1 of every pair, ..., then the question-token units the
+// same way.  Records of kind "none" pad every pair to the same count; their workgroups exit.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,49 +26,8 @@
 
 namespace mate {
 
-constexpr int BM = 128;            // owned rows per workgroup (32 per wavefront)
-constexpr int BN = 64;             // streamed rows per tile
 constexpr int kThreads = 256;
 constexpr int kFinalizeBlocks = 4; // workgroups per (b,h) in the finalize kernels (32 rows each, strided)
-constexpr int kMinChunkTiles = 8;  // streamed tiles per chunk of a question-token owner
-
-__host__ __device__ inline int owner_slots(int N) { return (N + BM - 1) / BM; }  // UG
-
-// How the streamed side of question-token owners is chunked (same answer in every kernel).
-struct GlobalSplit {
-  int n_gt;      // owner tiles of question tokens
-  int n_st;      // streamed tiles in total: question tiles then table tiles
-  int n_chunks;  // units per owner tile (>= 1); partial results are used iff n_chunks > 1
-  int per;       // streamed tiles per chunk
-};
-__device__ inline GlobalSplit global_split(int G, int L, int N) {
-  GlobalSplit s;
-  s.n_gt = (G + BM - 1) / BM;
-  s.n_st = (G + BN - 1) / BN + (L + BN - 1) / BN;
-  const int want = (s.n_st + kMinChunkTiles - 1) / kMinChunkTiles;
-  const int cap = s.n_gt ? owner_slots(N) / s.n_gt : 1;
-  const int n = max(1, min(want, cap));
-  s.per = (s.n_st + n - 1) / n;
-  s.n_chunks = s.per ? (s.n_st + s.per - 1) / s.per : 1;  // drop empty trailing chunks
-  return s;
-}
-
-// ---- plan buffer (ints, in the caller's workspace) -------------------------------------------
-//   [0, 16)    ticket counters: [kernel slot 0..1][queue 0..7]
-//   [32 + q]   tickets of queue q
-//   [40 + q]   (sequence, head) pairs of queue q: bh = q + 8 j, j < pairs
-//   [48 + q]   the largest number of table-token tiles of one of those pairs
-//   [64 + (2 q + k)(nq + 1) + j]  k = 0: exclusive prefix over the queue's pairs of their pad
-//              units, k = 1: of their question-token units; nq = ceil(B H / 8)
-// Ticket order of a queue: table-token tile 0 of every pair, tile 1 of every pair, ... (tickets
-// of pairs that have fewer tiles are empty), then the pad units, then the question-token units.
-constexpr int kPlanCounters = 0, kPlanTotal = 32, kPlanPairs = 40, kPlanMost = 48, kPlanPref = 64;
-__host__ __device__ inline int plan_nq(int BH) { return (BH + 7) >> 3; }
-__host__ __device__ inline size_t plan_words(int BH) {
-  return (size_t)kPlanPref + 16 * (size_t)(plan_nq(BH) + 1);
-}
-
-enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
 
 struct UnitPlan {
   int kind;
@@ -81,149 +42,58 @@ struct UnitPlan {
   int G, L, P;
 };
 
-__device__ inline UnitPlan plan_base(const AttnArgs& a, int b) {
-  const int* cnt = a.seg.counts + (size_t)b * kCountWords;
-  UnitPlan u;
-  u.kind = UNIT_NONE;
-  u.G = cnt[C_G];
-  u.L = cnt[C_L];
-  u.P = cnt[C_P];
-  u.part = -1;
-  u.n_t0 = (u.G + BN - 1) / BN;
-  u.t_begin = u.t_end = 0;
-  return u;
-}
-// Table-token owner described by `desc` = (first slot, streamed window lo, hi) of (b, view).
-__device__ inline UnitPlan plan_local(const AttnArgs& a, int b, int view, int4 desc) {
-  UnitPlan u = plan_base(a, b);
-  u.kind = UNIT_LOCAL;
-  u.t0 = desc.x;
-  u.own_list = a.seg.perm[view] + (size_t)b * a.N;
-  u.own_count = u.L;
-  u.str_list = u.own_list;
-  u.s_lo = desc.y;
-  u.s_hi = desc.z;
-  u.t_end = u.n_t0 + (u.s_hi - u.s_lo + BN - 1) / BN;
-  return u;
-}
-// Question-token unit number `gu` of sequence b: owner tile gu / n_chunks, chunk gu % n_chunks.
-__device__ inline UnitPlan plan_global(const AttnArgs& a, int b, int gu) {
-  UnitPlan u = plan_base(a, b);
-  const int N = a.N;
-  const GlobalSplit s = global_split(u.G, u.L, N);
-  const int gt = gu / s.n_chunks, c = gu % s.n_chunks;
-  u.kind = UNIT_GLOBAL;
-  u.t0 = gt * BM;
-  u.own_list = a.seg.global_idx + (size_t)b * N;
-  u.own_count = u.G;
-  u.str_list = a.seg.perm[0] + (size_t)b * N;  // row order: the contiguous one
-  u.s_lo = 0;
-  u.s_hi = u.L;
-  u.t_begin = c * s.per;
-  u.t_end = min(s.n_st, u.t_begin + s.per);
-  if (s.n_chunks > 1) u.part = gu;
-  return u;
-}
-__device__ inline UnitPlan plan_pad(const AttnArgs& a, int b, int tile) {
-  UnitPlan u = plan_base(a, b);
-  u.kind = UNIT_PAD;
-  u.t0 = tile * BM;
-  u.own_list = a.seg.pad_idx + (size_t)b * a.N;
-  u.own_count = u.P;
-  return u;
-}
-
-// Development aid (compiled out unless MATE_TRACE is defined): one record per unit with its
-// start / end time (100 MHz wall clock), hardware placement and description.
-#ifdef MATE_TRACE
-#define MATE_TRACE_BEGIN const long long t_start_ = wall_clock64();
-#define MATE_TRACE_END(kernel_no, q, t, info)                                              \
-  if (a.trace && threadIdx.x == 0 && (t) < 8192) {                                         \
-    long long* r_ = a.trace + ((size_t)(kernel_no) * (1 << 16) + (q) * 8192 + (t)) * 4;    \
-    r_[0] = t_start_;                                                                      \
-    r_[1] = wall_clock64();                                                                \
-    r_[2] = (info);                                                                        \
-    r_[3] = ((long long)__builtin_amdgcn_s_getreg(63508) << 32) |                          \
-            (unsigned)__builtin_amdgcn_s_getreg(63492);                                    \
-  }
-#else
-#define MATE_TRACE_BEGIN
-#define MATE_TRACE_END(kernel_no, q, t, info) (void)(info);
-#endif
-
-// ---- work queues -------------------------------------------------------------------------------
+// ---- workgroup -> unit ---------------------------------------------------------------------
 struct Work {
   int bh, view;
   UnitPlan u;
 };
 
-__device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7; }  // XCC_ID[3:0]
+inline int unit_grid(int B, int H, int N) {
+  return 8 * ((B * H + 7) / 8) * (2 * owner_slots(N) + 2);
+}
 
-// Ticket `t` of queue `q` -> which (b,h), which unit (kind UNIT_NONE: an empty ticket).  All
-// inputs wave-uniform.
-__device__ inline Work decode_ticket(const AttnArgs& a, int q, int t) {
-  const int nq = plan_nq(a.B * a.H);
-  const int pairs = a.plan[kPlanPairs + q], most = a.plan[kPlanMost + q];
-  Work w;
-  if (t < pairs * most) {
-    const int j = t % pairs, k = t / pairs;
-    w.bh = q + 8 * j;
-    const int b = w.bh / a.H;
-    w.view = a.head_kind[w.bh % a.H];
-    const int4 desc = a.seg.tile_desc[w.view][(size_t)b * a.seg.tiles + k];
-    if (desc.x < 0) w.u.kind = UNIT_NONE;
-    else w.u = plan_local(a, b, w.view, desc);
-    return w;
-  }
-  t -= pairs * most;
-  const int* pref = a.plan + kPlanPref + 2 * q * (nq + 1);
-  const int is_global = t >= pref[nq];
-  if (is_global) {
-    t -= pref[nq];
-    pref += nq + 1;
-  }
-  int lo = 0, hi = nq;  // largest j with pref[j] <= t
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (pref[mid] <= t) lo = mid; else hi = mid;
-  }
-  w.bh = q + 8 * lo;
+// Returns false if this workgroup has nothing to do.  Everything here is wave-uniform and
+// stays in scalar registers.
+__device__ inline bool take_unit(const AttnArgs& a, Work& w) {
+  const int T = a.seg.tiles, N = a.N;
+  const int q = blockIdx.x & 7, pairs = (a.B * a.H - q + 7) >> 3;
+  int t = blockIdx.x >> 3;
+  if (pairs <= 0) return false;
+  const int n_lp = pairs * (T + 2);
+  const bool glob = t >= n_lp;
+  if (glob) t -= n_lp;
+  // The hardware hands consecutive workgroups of an XCD to its shader engines in rotation and
+  // stalls when the engine whose turn it is has no room, so each engine must see the same mix
+  // of long (column-head) and short (row-head) units: the pair order rotates from sweep to sweep.
+  const int k = t / pairs, j = (t + k) % pairs;
+  if (glob && k >= T) return false;
+  w.bh = q + 8 * j;
   const int b = w.bh / a.H;
   w.view = a.head_kind[w.bh % a.H];
-  w.u = is_global ? plan_global(a, b, t - pref[lo]) : plan_pad(a, b, t - pref[lo]);
-  return w;
+  const int4* rec = glob ? a.seg.gunit + ((size_t)b * T + k) * 2
+                         : a.seg.unit[w.view] + ((size_t)b * (T + 2) + k) * 2;
+  const int4 r0 = rec[0], r1 = rec[1];
+  const int* cnt = a.seg.counts + (size_t)b * kCountWords;
+  UnitPlan& u = w.u;
+  u.kind = r0.x;
+  if (u.kind == UNIT_NONE) return false;
+  u.t0 = r0.y;
+  u.s_lo = r0.z;
+  u.s_hi = r0.w;
+  u.t_begin = r1.x;
+  u.t_end = r1.y;
+  u.part = r1.z;
+  u.G = cnt[C_G];
+  u.L = cnt[C_L];
+  u.P = cnt[C_P];
+  u.n_t0 = (u.G + BN - 1) / BN;
+  const int* perm_v = a.seg.perm[w.view] + (size_t)b * N;
+  u.str_list = glob ? a.seg.perm[0] + (size_t)b * N : perm_v;  // row order: the contiguous one
+  u.own_list = glob ? a.seg.global_idx + (size_t)b * N
+                    : u.kind == UNIT_LOCAL ? perm_v : a.seg.pad_idx + (size_t)b * N;
+  u.own_count = glob ? u.G : u.kind == UNIT_LOCAL ? u.L : u.P;
+  return true;
 }
-
-// One unit per workgroup: draw a ticket from the queue of this workgroup's XCD, or, if that
-// queue is exhausted, from the others in turn.  The host launches as many workgroups as there
-// can be units (upper bound from B, H, N); the surplus finds every queue empty and exits.
-// (A persistent loop over tickets was tried and lost: with the unit body inside a loop the
-// compiler runs out of scalar registers and moves the wave-uniform bookkeeping into vector
-// registers and vector ALU work; the hardware's workgroup dispatcher is the faster loop.)
-// Returns false if there is nothing left to do.
-__device__ inline bool take_unit(const AttnArgs& a, int kernel_slot, Work& w, int& queue, int& ticket) {
-  __shared__ int s_ticket, s_queue;
-  if (threadIdx.x == 0) {
-    int* counters = a.plan + kPlanCounters + 8 * kernel_slot;
-    int q = xcc_id(), t = -1;
-    for (int tried = 0; tried < 8; ++tried, q = (q + 1) & 7) {
-      if (counters[q] >= a.plan[kPlanTotal + q]) continue;  // looks exhausted: do not bump it
-      t = atomicAdd(&counters[q], 1);
-      if (t < a.plan[kPlanTotal + q]) break;
-      t = -1;
-    }
-    s_ticket = t;
-    s_queue = q;
-  }
-  __syncthreads();
-  // wave-uniform values: keep the whole unit description in scalar registers
-  ticket = __builtin_amdgcn_readfirstlane(s_ticket);
-  queue = __builtin_amdgcn_readfirstlane(s_queue);
-  if (ticket < 0) return false;
-  w = decode_ticket(a, queue, ticket);
-  return w.u.kind != UNIT_NONE;
-}
-inline int units_upper_bound(int B, int H, int N) { return B * H * (2 * owner_slots(N) + 1); }
 
 // Streamed tile t of a unit: which index list, first slot, last valid slot.
 __device__ inline void tile_source(const UnitPlan& u, const int* global_idx, int t,
@@ -313,11 +183,6 @@ __device__ inline void zero_pad_rows(unsigned short* __restrict__ out, const Uni
       *reinterpret_cast<uint4*>(out + (size_t)u.own_list[u.t0 + row] * kD + piece * 8) =
           make_uint4(0, 0, 0, 0);
   }
-}
-
-// what a unit body reports to the trace: kind | streamed tiles << 4
-__device__ inline int unit_info(const UnitPlan& u) {
-  return u.kind | ((u.kind == UNIT_GLOBAL || u.kind == UNIT_LOCAL ? u.t_end - u.t_begin : 0) << 4);
 }
 
 __device__ inline bool tables_match(const AttnArgs& a) {
