@@ -27,7 +27,7 @@ constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
 
 __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
-  __shared__ int idx_ring[4][kIdxSlots][BN];  // [wavefront][tile & 7][row] token positions
+  __shared__ int idx_ring[kIdxSlots][BN];  // [tile & 7][row] token positions
   __shared__ int q_tok[BM];
 
   const int b = w.bh / a.H;
@@ -64,7 +64,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
   // ---- streaming: K and V tiles go straight from global memory into a ring of LDS stages
-  TileStream<kStageBytes> stream(u, global_idx, lds, idx_ring[wave], K, V, nullptr, 0, wave, lane);
+  TileStream<kStageBytes> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
   stream.prologue();
   const int tb = u.t_begin, te = u.t_end;
   // Everything loaded into registers so far is pinned as complete here, so that no load with a

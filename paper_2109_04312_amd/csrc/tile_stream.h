@@ -2,12 +2,14 @@
 // holding one 64-row tile of two tensors (plus, optionally, one float per row of a third
 // array), filled NS - 1 tiles ahead of the compute by asynchronous global->LDS loads.
 //
-// The token indices of a tile's 64 rows travel the same way (one word per lane into a
-// per-wavefront ring), a further NS - 1 tiles ahead, so no load of the loop has a register
-// destination and the only waits are the explicit ones in acquire().  `since[k]` counts this
-// wavefront's vector loads issued after the data loads of tile (current + k); an index load
-// is issued just before the data loads of the same iteration, so waiting for a tile's data
-// also retires every index load issued before it.
+// The token indices of a tile's 64 rows travel the same way (one word per lane into a ring
+// shared by the workgroup; wavefront t mod 4 fetches the indices of tile t), a further NS - 1
+// tiles ahead, so no load of the loop has a register destination and the only waits are the
+// explicit ones in acquire().  `since[k]` counts this wavefront's vector loads issued after
+// the data loads of tile (current + k).  An index load is issued just before the data loads of
+// the same iteration, so the wait for that tile's data NS - 1 iterations later also retires
+// it, and the barrier that follows the wait publishes it to the other wavefronts -- in the very
+// iteration that first reads it.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -16,7 +18,7 @@
 
 namespace mate {
 
-constexpr int NS = 4;         // ring stages: tiles in flight + the one being consumed
+constexpr int NS = 3;         // ring stages: tiles in flight + the one being consumed
 constexpr int kIdxSlots = 8;  // >= NS + 1 tiles of indices live at once (power of two)
 
 template <int kStageBytes>
@@ -24,7 +26,7 @@ struct TileStream {
   const UnitPlan& u;
   const int* global_idx;
   char* stages;               // NS * kStageBytes of LDS
-  int (*ring)[BN];            // this wavefront's index ring [kIdxSlots][64]
+  int (*ring)[BN];            // the workgroup's index ring [kIdxSlots][64]
   const unsigned short* X0;   // tensor staged at stage offset 0
   const unsigned short* X1;   // tensor staged at stage offset kTileBytes
   const float* row_src;       // optional: one float per streamed row -> stage offset row_off
@@ -48,6 +50,7 @@ struct TileStream {
   }
   __device__ void issue_idx(int t) {
     const int* list; int base, last;
+    if (wave != (t & 3)) return;
     tile_source(u, global_idx, t, list, base, last);
     issue_row_words(list + min(base + lane, last), &ring[t & (kIdxSlots - 1)][0]);
     note(1);
@@ -71,6 +74,7 @@ struct TileStream {
     for (int s = 0; s < 2 * NS - 2; ++s)
       if (u.t_begin + s < u.t_end) issue_idx(u.t_begin + s);
     wait_vmcnt_le(0);
+    barrier_no_fence();  // every wavefront's share of the first indices is in the ring
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
       if (u.t_begin + s < u.t_end) issue_data(u.t_begin + s, s);
