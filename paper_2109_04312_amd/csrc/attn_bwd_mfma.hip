@@ -29,10 +29,11 @@ namespace {
 // dQ (and delta)
 // ======================================================================================
 constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
+constexpr int kDqNS = 3, kDkvNS = 2;              // LDS stages of the two kernels
 constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, lse[64], delta[64]
 
 __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
-  __shared__ __attribute__((aligned(1024))) char lds[NS * kDqStage];
+  __shared__ __attribute__((aligned(1024))) char lds[kDqNS * kDqStage];
   __shared__ int idx_ring[kIdxSlots][BN];
   __shared__ int q_tok[BM];
 
@@ -79,7 +80,7 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
 
   // K and V tiles stream through the LDS ring; K is read both plain (S^T = K Q^T) and
   // transposed (dQ^T += K^T dS^T), V plain (dP^T = V dO^T).
-  TileStream<kDqStage> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
+  TileStream<kDqStage, kDqNS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
   stream.prologue();
   asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(gf[0]), "v"(gf[1]),
                "v"(gf[2]), "v"(gf[3]), "v"(me.lo), "v"(me.hi), "v"(lse2), "v"(delta));
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
 // dK, dV
 // ======================================================================================
 __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
-  __shared__ __attribute__((aligned(1024))) char lds[NS * kDkvStage];
+  __shared__ __attribute__((aligned(1024))) char lds[kDkvNS * kDkvStage];
   __shared__ int idx_ring[kIdxSlots][BN];
   __shared__ int k_tok[BM];
 
@@ -200,7 +201,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   // (S = Q K^T, dP = dO V^T) and transposed (dK^T += Q^T dS, dV^T += dO^T P); wavefront 0
   // also brings the queries' lse, wavefront 1 their delta (one float per row).
   const float* row_src = wave == 0 ? a.lse + bh : wave == 1 ? a.delta + bh : nullptr;
-  TileStream<kDkvStage> stream(u, global_idx, lds, idx_ring, Q, dO, row_src,
+  TileStream<kDkvStage, kDkvNS> stream(u, global_idx, lds, idx_ring, Q, dO, row_src,
                                2 * kTileBytes + 256 * wave, wave, lane);
   stream.prologue();
   asm volatile("" ::"v"(kf[0]), "v"(kf[1]), "v"(kf[2]), "v"(kf[3]), "v"(vf[0]), "v"(vf[1]),

@@ -24,6 +24,7 @@ namespace mate {
 namespace {
 
 constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
+constexpr int NS = 2;  // LDS stages: small enough for four workgroups per CU
 
 __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[NS * kStageBytes];
@@ -64,7 +65,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
   // ---- streaming: K and V tiles go straight from global memory into a ring of LDS stages
-  TileStream<kStageBytes> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
+  TileStream<kStageBytes, NS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
   stream.prologue();
   const int tb = u.t_begin, te = u.t_end;
   // Everything loaded into registers so far is pinned as complete here, so that no load with a
@@ -160,7 +161,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   store_owned_rows(o_acc, 1.f / l_tot, reinterpret_cast<unsigned short*>(lds), O, q_tok, wave, lane);
 }
 
-__global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 4) void fwd_mfma_kernel(AttnArgs a) {
   Work w;
   if (!take_unit(a, w)) return;
   fwd_unit(a, w);

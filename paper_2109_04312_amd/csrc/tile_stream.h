@@ -18,10 +18,10 @@
 
 namespace mate {
 
-constexpr int NS = 3;         // ring stages: tiles in flight + the one being consumed
-constexpr int kIdxSlots = 8;  // >= NS + 1 tiles of indices live at once (power of two)
+constexpr int kIdxSlots = 8;  // >= 2 NS - 1 tiles of indices live at once (power of two)
 
-template <int kStageBytes>
+// NS = ring stages: tiles in flight + the one being consumed (2 <= NS <= 4).
+template <int kStageBytes, int NS>
 struct TileStream {
   const UnitPlan& u;
   const int* global_idx;
