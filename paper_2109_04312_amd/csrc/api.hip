@@ -35,10 +35,16 @@ mate_status fill_args(AttnArgs& a, const void* segments, const uint8_t* head_kin
   if (D != MATE_HEAD_DIM || (t != MATE_F32 && t != MATE_BF16)) return MATE_ERR_UNSUPPORTED;
   if (!(scale > 0.f) || !(scale < 3.0e38f)) return MATE_ERR_UNSUPPORTED;
   std::memset(&a, 0, sizeof(a));
+  int n_sorted = 0;
   for (int h = 0; h < H; ++h) {
     if (head_kind[h] > MATE_HEAD_COL) return MATE_ERR_UNSUPPORTED;
     a.head_kind[h] = head_kind[h];
   }
+  for (int kind = MATE_HEAD_COL; kind >= MATE_HEAD_ROW; --kind)
+    for (int h = 0; h < H; ++h)
+      if (head_kind[h] == kind) a.head_order[n_sorted++] = (unsigned char)h;
+  a.n_col = 0;
+  for (int h = 0; h < H; ++h) a.n_col += head_kind[h] == MATE_HEAD_COL;
   a.seg = make_tables(segments, B, N);
   a.B = B;
   a.H = H;

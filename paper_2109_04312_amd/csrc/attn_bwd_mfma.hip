@@ -343,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
-  const dim3 grid(unit_grid(a.B, a.H, a.N)), block(kThreads);
+  const dim3 grid(unit_grid(a.B, a.H, a.N, a.n_col)), block(kThreads);
   hipError_t e;
   {
     ProfileScope prof(3, stream);

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream) {
   {
     ProfileScope prof(2, stream);
-    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(unit_grid(a.B, a.H, a.N)), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(unit_grid(a.B, a.H, a.N, a.n_col)), dim3(kThreads), 0, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -18,6 +18,8 @@ struct AttnArgs {
   float* part_ml;           // forward: running max (log2 domain) and sum per partial row
   SegTables seg;
   unsigned char head_kind[256];
+  unsigned char head_order[256];  // heads sorted column heads first (stable)
+  int n_col;                      // number of column heads
   int B, H, N;
   float scale;
 };

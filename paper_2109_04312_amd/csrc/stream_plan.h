@@ -15,9 +15,12 @@
 // Workgroup -> unit is arithmetic on the workgroup index plus one record read: no counters, no
 // atomics, no dependent loads.  Workgroup i serves queue i mod 8 (consecutive workgroups go to
 // consecutive XCDs, so a queue stays on one XCD and the units of one (sequence, head) pair
-// share an L2); queue q holds the pairs b H + h = q mod 8.  Order inside a queue: table-token
-// (then pad) tile 0 of every pair, tile 1 of every pair, ..., then the question-token units the
-// same way.  Records of kind "none" pad every pair to the same count; their workgroups exit.
+// share an L2).  Column-head pairs are numbered c = b n_col + i and belong to queue c mod 8, row-
+// head pairs r = b n_row + i to queue r mod 8.  Order inside a queue, longest units first:
+//   1. column heads: table-token (then pad) tile 0 of every pair, tile 1 of every pair, ...
+//   2. question-token units of all pairs, the same way
+//   3. row heads, as in 1
+// Records of kind "none" pad every pair to the same count; their workgroups exit at once.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -48,28 +51,53 @@ struct Work {
   UnitPlan u;
 };
 
-inline int unit_grid(int B, int H, int N) {
-  return 8 * ((B * H + 7) / 8) * (2 * owner_slots(N) + 2);
+inline int unit_grid(int B, int H, int N, int n_col) {
+  const int T = owner_slots(N), nc = (B * n_col + 7) / 8, nr = (B * (H - n_col) + 7) / 8;
+  return 8 * ((nc + nr) * (T + 2) + (nc + nr) * T);
 }
 
 // Returns false if this workgroup has nothing to do.  Everything here is wave-uniform and
 // stays in scalar registers.
 __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
-  const int T = a.seg.tiles, N = a.N;
-  const int q = blockIdx.x & 7, pairs = (a.B * a.H - q + 7) >> 3;
+  const int T = a.seg.tiles, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
+  const int q = blockIdx.x & 7;
+  const int nc = (a.B * n_col - q + 7) >> 3, nr = (a.B * n_row - q + 7) >> 3;  // pairs of this queue
   int t = blockIdx.x >> 3;
+  // region -> (first pair, pairs, records per pair)
+  int first = 0, pairs = nc, per = T + 2;
+  bool glob = false;
+  if (t >= nc * (T + 2)) {
+    t -= nc * (T + 2);
+    pairs = nc + nr;
+    per = T;
+    glob = true;
+    if (t >= pairs * T) {
+      t -= pairs * T;
+      first = nc;
+      pairs = nr;
+      per = T + 2;
+      glob = false;
+    }
+  }
   if (pairs <= 0) return false;
-  const int n_lp = pairs * (T + 2);
-  const bool glob = t >= n_lp;
-  if (glob) t -= n_lp;
   // The hardware hands consecutive workgroups of an XCD to its shader engines in rotation and
   // stalls when the engine whose turn it is has no room, so each engine must see the same mix
-  // of long (column-head) and short (row-head) units: the pair order rotates from sweep to sweep.
-  const int k = t / pairs, j = (t + k) % pairs;
-  if (glob && k >= T) return false;
-  w.bh = q + 8 * j;
-  const int b = w.bh / a.H;
-  w.view = a.head_kind[w.bh % a.H];
+  // of units: the pair order rotates from sweep to sweep.
+  const int k = t / pairs, j = first + (t + k) % pairs;
+  if (k >= per) return false;
+  int b, h;
+  if (j < nc) {
+    const int c = q + 8 * j;
+    b = c / n_col;
+    h = a.head_order[c % n_col];
+    w.view = 1;
+  } else {
+    const int r = q + 8 * (j - nc);
+    b = r / n_row;
+    h = a.head_order[n_col + r % n_row];
+    w.view = 0;
+  }
+  w.bh = b * a.H + h;
   const int4* rec = glob ? a.seg.gunit + ((size_t)b * T + k) * 2
                          : a.seg.unit[w.view] + ((size_t)b * (T + 2) + k) * 2;
   const int4 r0 = rec[0], r1 = rec[1];

@@ -35,13 +35,21 @@ def run_hip(w: synth.Workload, backward: bool):
     r, c, f = dev_structure(w.structure)
     seg = mate.build_segments(r, c, f)
     q, k, v = (to_dev(x, w.dtype) for x in (w.q, w.k, w.v))
-    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale)
+    # outputs start as NaN: a row that no workgroup writes cannot pass for a result
+    nan_like = lambda t: torch.full_like(t, float("nan"))
+    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale, out=nan_like(q),
+                             lse=torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=q.device))
     res = dict(o=out, lse=lse)
     if backward:
         do = to_dev(w.do, w.dtype)
-        dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale)
+        dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale,
+                                   dq=nan_like(q), dk=nan_like(q), dv=nan_like(q))
         res.update(dq=dq, dk=dk, dv=dv)
     torch.cuda.synchronize()
+    pad = torch.from_numpy(w.structure.flags == synth.TOK_PAD).to(q.device)[:, None, :].expand(q.shape[:3])
+    for name, t in res.items():
+        assert bool(torch.isfinite(t).all()), f"{name}: some (b, h, position) was never written"
+        assert bool((t[pad] == 0).all()), f"{name}: pad positions must be zero in every head"
     return {n: t.float().cpu().numpy().astype(np.float64) for n, t in res.items()}, seg
 
 

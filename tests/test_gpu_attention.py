@@ -125,6 +125,14 @@ def test_head_kind_mix_and_order():
     check_workload(w, backward=True)
 
 
+@pytest.mark.parametrize("kinds", [(ROW, ROW, ROW), (COL, COL, COL), (ROW, COL, COL)])
+def test_single_kind_and_odd_pair_counts(kinds):
+    # only row heads / only column heads; B * H = 9 is not a multiple of the eight work queues
+    w = small_workload(11, "bf16", B=3, N=300, H=3, max_rows=12, max_cols=5, max_global=20)
+    w.head_kind = np.array(kinds, np.uint8)
+    check_workload(w, backward=True, label=f"kinds{kinds}")
+
+
 def test_argument_errors_leave_outputs_untouched():
     from paper_2109_04312_amd import mate
     w = small_workload(1, "f32", B=1, N=64, H=2, bwd=False)
