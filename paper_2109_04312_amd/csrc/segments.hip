@@ -23,6 +23,13 @@ namespace mate {
 constexpr int kSegThreads = 1024;
 constexpr int kSegWaves = kSegThreads / 64;
 
+// Workgroup barrier for data exchanged through LDS only: waits for this wavefront's LDS traffic,
+// not for its global stores (a full fence would stall every phase on store round trips; nothing
+// the kernel writes to global memory is read back inside it).
+__device__ inline void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Exclusive prefix sum of one int per thread across the workgroup; `total` gets the sum.
 // `tmp` is kSegWaves + 1 ints of LDS.  Ends with a barrier so `tmp` can be reused at once.
 __device__ inline int block_exclusive_scan(int v, int* tmp, int& total) {
@@ -34,7 +41,7 @@ __device__ inline int block_exclusive_scan(int v, int* tmp, int& total) {
     if (lane >= d) inc += up;
   }
   if (lane == 63) tmp[wave] = inc;
-  __syncthreads();
+  lds_barrier();
   int base = 0, tot = 0;
 #pragma unroll
   for (int w = 0; w < kSegWaves; ++w) {
@@ -42,24 +49,37 @@ __device__ inline int block_exclusive_scan(int v, int* tmp, int& total) {
     if (w < wave) base += s;
     tot += s;
   }
-  __syncthreads();
+  lds_barrier();
   total = tot;
   return base + inc - v;
+}
+
+// Lanes of the wavefront that hold the same 8-bit digit as this lane (valid lanes only).
+__device__ inline unsigned long long match_digit(unsigned digit, bool valid) {
+  unsigned long long same = __ballot(valid);
+#pragma unroll
+  for (int bit = 0; bit < 8; ++bit) {
+    const bool one = (digit >> bit) & 1u;
+    const unsigned long long m = __ballot(one);
+    same &= one ? m : ~m;
+  }
+  return same;
 }
 
 template <int P2>
 __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int* __restrict__ row_ids, const int* __restrict__ col_ids,
     const unsigned char* __restrict__ flags, int B, int N, int* __restrict__ seg) {
-  constexpr int PER = P2 / kSegThreads;  // consecutive elements owned by one thread
   constexpr int CHUNK = P2 / kSegWaves;  // consecutive elements owned by one wavefront
-  static_assert(PER >= 1, "P2 must be at least the workgroup size");
+  constexpr int NB = CHUNK / 64;         // 64-element batches per wavefront
+  static_assert(NB >= 1, "P2 must be at least the workgroup size");
   __shared__ int ids[P2];                  // id by token position; later: segment starts (ushort)
   __shared__ unsigned short buf_a[P2];     // current order of table-token positions
   __shared__ unsigned short buf_b[P2];     // next order; later: segment index by slot
   __shared__ int hist[kSegWaves][256];     // per-wavefront digit counts -> running output slots
   __shared__ int scan_tmp[kSegWaves + 1];
-  __shared__ int s_or;
+  __shared__ int wave_tot[3][kSegWaves];
+  __shared__ int s_or, s_bad;
 
   const int b = blockIdx.x, view = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -79,14 +99,21 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
 
   if (b == 0 && view == 0 && tid < kHdrWords)
     seg[tid] = tid == 0 ? kMagic : tid == 1 ? B : tid == 2 ? N : 0;
-  if (tid == 0) s_or = 0;
+  if (tid == 0) { s_or = 0; s_bad = 0; }
+  lds_barrier();
 
-  // ---- classify; compact the three kinds of position in ascending order -------------------
+  // Element order everywhere below: a wavefront owns CHUNK consecutive elements and walks them in
+  // batches of 64, lane = consecutive element, so that LDS and global accesses are unit-stride
+  // and ranks inside a batch come from ballots.
+  const int w0 = wave * CHUNK;
+  const unsigned long long below = (1ull << lane) - 1ull;  // lanes before this one
+
+  // ---- classify; count the three kinds of position per wavefront ---------------------------
+  unsigned char my_flag[NB];
   int n_g = 0, n_p = 0, n_l = 0, bad = 0, my_or = 0;
-  unsigned char my_flag[PER];
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int i = tid * PER + e;
+  for (int e = 0; e < NB; ++e) {
+    const int i = w0 + e * 64 + lane;
     unsigned char f = 3;
     if (i < N) {
       f = fl[i];
@@ -96,51 +123,74 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
         if (id < 0) bad = 1;
         ids[i] = id;
         my_or |= id;
-        ++n_l;
       } else {
         seg_of_tok[i] = -1;
-        if (f == 1) ++n_g; else ++n_p;
       }
     }
     my_flag[e] = f;
+    n_l += __popcll(__ballot(f == 0));
+    n_g += __popcll(__ballot(f == 1));
+    n_p += __popcll(__ballot(f == 2));
   }
-  int G, P, L;
-  int g_at = block_exclusive_scan(n_g, scan_tmp, G);
-  int p_at = block_exclusive_scan(n_p, scan_tmp, P);
-  int l_at = block_exclusive_scan(n_l, scan_tmp, L);
-  const int any_bad = __syncthreads_or(bad);
-  if (my_or) atomicOr(&s_or, my_or);
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int i = tid * PER + e;
-    if (my_flag[e] == 0) buf_a[l_at++] = (unsigned short)i;
+  for (int d = 32; d >= 1; d >>= 1) my_or |= __shfl_xor(my_or, d, 64);
+  if (lane == 0) {
+    wave_tot[0][wave] = n_l;
+    wave_tot[1][wave] = n_g;
+    wave_tot[2][wave] = n_p;
+    if (my_or) atomicOr(&s_or, my_or);
+  }
+  if (bad) s_bad = 1;
+  lds_barrier();
+  int L = 0, G = 0, P = 0, l_at = 0, g_at = 0, p_at = 0;
+#pragma unroll
+  for (int w = 0; w < kSegWaves; ++w) {
+    const int cl = wave_tot[0][w], cg = wave_tot[1][w], cp = wave_tot[2][w];
+    if (w < wave) { l_at += cl; g_at += cg; p_at += cp; }
+    L += cl; G += cg; P += cp;
+  }
+  const unsigned all_bits = (unsigned)s_or;
+
+  // ---- compact the three kinds in ascending position order ------------------------------------
+#pragma unroll
+  for (int e = 0; e < NB; ++e) {
+    const int i = w0 + e * 64 + lane;
+    const unsigned long long ml = __ballot(my_flag[e] == 0), mg = __ballot(my_flag[e] == 1),
+                             mp = __ballot(my_flag[e] == 2);
+    if (my_flag[e] == 0) buf_a[l_at + __popcll(ml & below)] = (unsigned short)i;
     if (view == 0) {
-      if (my_flag[e] == 1) global_idx[g_at++] = i;
-      if (my_flag[e] == 2) pad_idx[p_at++] = i;
+      if (my_flag[e] == 1) global_idx[g_at + __popcll(mg & below)] = i;
+      if (my_flag[e] == 2) pad_idx[p_at + __popcll(mp & below)] = i;
     }
+    l_at += __popcll(ml);
+    g_at += __popcll(mg);
+    p_at += __popcll(mp);
   }
   if (view == 0) {
     for (int i = G + tid; i < N; i += kSegThreads) global_idx[i] = -1;
     for (int i = P + tid; i < N; i += kSegThreads) pad_idx[i] = -1;
     if (tid == 0) { counts[C_G] = G; counts[C_L] = L; counts[C_P] = P; }
   }
-  if (tid == 0) counts[5 + view] = any_bad;
-  __syncthreads();
-  const unsigned all_bits = (unsigned)s_or;
+  if (tid == 0) counts[5 + view] = s_bad;
+  lds_barrier();
 
   // ---- stable LSD radix sort of buf_a[0..L) by ids[position] --------------------------------
   unsigned short* cur = buf_a;
   unsigned short* nxt = buf_b;
+  const int w_hi = min(w0 + CHUNK, L);
   for (int shift = 0; shift < 32; shift += 8) {
     if (((all_bits >> shift) & 255u) == 0) continue;  // this digit is 0 everywhere: order unchanged
     for (int i = tid; i < kSegWaves * 256; i += kSegThreads) (&hist[0][0])[i] = 0;
-    __syncthreads();
-    const int w_lo = wave * CHUNK, w_hi = min(w_lo + CHUNK, L);
-    for (int s0 = w_lo; s0 < w_hi; s0 += 64) {
+    lds_barrier();
+    for (int s0 = w0; s0 < w_hi; s0 += 64) {
       const int s = s0 + lane;
-      if (s < w_hi) atomicAdd(&hist[wave][((unsigned)ids[cur[s]] >> shift) & 255u], 1);
+      const bool valid = s < w_hi;
+      const unsigned digit = valid ? ((unsigned)ids[cur[s]] >> shift) & 255u : 0u;
+      const unsigned long long same = match_digit(digit, valid);
+      // one add per group of equal digits (neighbouring tokens mostly share a digit)
+      if (valid && (same & below) == 0) hist[wave][digit] += __popcll(same);
     }
-    __syncthreads();
+    lds_barrier();
     // counts -> first output slot of (digit, wavefront): digits ascending, wavefronts ascending
     int tot = 0;
     if (tid < 256) {
@@ -154,74 +204,76 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int digit_base = block_exclusive_scan(tot, scan_tmp, all);
     if (tid < 256)
       for (int w = 0; w < kSegWaves; ++w) hist[w][tid] += digit_base;
-    __syncthreads();
+    lds_barrier();
     // rank inside each 64-element batch in lane order; batches of a wavefront go in sequence
-    for (int s0 = w_lo; s0 < w_hi; s0 += 64) {
+    for (int s0 = w0; s0 < w_hi; s0 += 64) {
       const int s = s0 + lane;
       const bool valid = s < w_hi;
       const unsigned pos = valid ? cur[s] : 0u;
       const unsigned digit = valid ? ((unsigned)ids[pos] >> shift) & 255u : 0u;
-      unsigned long long same = __ballot(valid);
-#pragma unroll
-      for (int bit = 0; bit < 8; ++bit) {
-        const bool one = (digit >> bit) & 1u;
-        const unsigned long long m = __ballot(one);
-        same &= one ? m : ~m;
-      }
+      const unsigned long long same = match_digit(digit, valid);
       if (valid) {
-        const int rank = __popcll(same & ((1ull << lane) - 1ull));
+        const int rank = __popcll(same & below);
         const int base = hist[wave][digit];
         nxt[base + rank] = (unsigned short)pos;
         if (rank == __popcll(same) - 1) hist[wave][digit] = base + __popcll(same);
       }
     }
-    __syncthreads();
+    lds_barrier();
     unsigned short* t = cur; cur = nxt; nxt = t;
   }
 
   // ---- run boundaries -> segment index per slot ----------------------------------------------
-  int head[PER], my_pos[PER];
+  unsigned head_bits = 0;  // bit e: my slot of batch e starts a segment
+  int my_pos[NB];
   int n_head = 0;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int s = tid * PER + e;
-    head[e] = 0;
-    my_pos[e] = 0;
-    if (s < L) {
-      my_pos[e] = cur[s];
-      head[e] = (s == 0) || (ids[cur[s - 1]] != ids[my_pos[e]]);
-      n_head += head[e];
-    }
+  for (int e = 0; e < NB; ++e) {
+    const int s = w0 + e * 64 + lane;
+    my_pos[e] = s < L ? cur[s] : 0;
+    const bool head = s < L && (s == 0 || ids[cur[s - 1]] != ids[my_pos[e]]);
+    head_bits |= (unsigned)head << e;
+    n_head += __popcll(__ballot(head));
   }
-  int S;
-  int seg_idx = block_exclusive_scan(n_head, scan_tmp, S) - 1;  // ends with a barrier
+  if (lane == 0) wave_tot[0][wave] = n_head;
+  lds_barrier();  // also: every wavefront is done reading ids[]
+  int S = 0, seg_at = 0;
+#pragma unroll
+  for (int w = 0; w < kSegWaves; ++w) {
+    const int c = wave_tot[0][w];
+    if (w < wave) seg_at += c;
+    S += c;
+  }
   // ids[] and the spare order buffer are dead now: reuse them
   unsigned short* seg_start = reinterpret_cast<unsigned short*>(ids);  // [P2], entry S (== L) implied
   unsigned short* seg_of_slot = nxt;                                    // [P2]
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int s = tid * PER + e;
+  for (int e = 0; e < NB; ++e) {
+    const int s = w0 + e * 64 + lane;
+    const bool head = (head_bits >> e) & 1u;
+    const unsigned long long mh = __ballot(head);
+    const int seg_idx = seg_at + __popcll(mh & below) + (head ? 1 : 0) - 1;  // heads up to and including me
     if (s < L) {
-      seg_idx += head[e];
       perm[s] = my_pos[e];
       seg_of_tok[my_pos[e]] = seg_idx;
       seg_of_slot[s] = (unsigned short)seg_idx;
-      if (head[e]) { seg_start[seg_idx] = (unsigned short)s; seg_off[seg_idx] = s; }
+      if (head) { seg_start[seg_idx] = (unsigned short)s; seg_off[seg_idx] = s; }
     } else if (s < N) {
       perm[s] = -1;
     }
+    seg_at += __popcll(mh);
   }
   if (tid == 0) { seg_off[S] = L; counts[C_SROW + view] = S; }
   for (int i = S + 1 + tid; i <= N; i += kSegThreads) seg_off[i] = -1;
-  __syncthreads();
+  lds_barrier();
   auto seg_lo = [&](int s) { return (int)seg_start[seg_of_slot[s]]; };
   auto seg_hi = [&](int s) {
     const int g = seg_of_slot[s];
     return g + 1 < S ? (int)seg_start[g + 1] : L;
   };
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int s = tid * PER + e;
+  for (int e = 0; e < NB; ++e) {
+    const int s = w0 + e * 64 + lane;
     if (s < N) slot_rng[s] = s < L ? make_int2(seg_lo(s), seg_hi(s)) : make_int2(0, 0);
   }
 
