@@ -4,10 +4,10 @@
 // whole sort lives in LDS.
 //
 // Sort: table-token positions are first compacted in ascending order, then reordered by a
-// least-significant-digit radix sort on their id, 8 bits per pass.  Each pass is stable (every
+// least-significant-digit radix sort on their id, 9 bits per pass.  Each pass is stable (every
 // wavefront owns a contiguous block of the current order, counts its digits, and ranks equal
 // digits inside a 64-element batch in lane order with ballots), so ties keep ascending position.
-// Passes whose digit is zero for every id are skipped: ids below 65536 cost two passes.
+// Passes whose digit is zero for every id are skipped: ids below 512 cost one pass.
 //
 // The kernel also lists the work units of the attention kernels per (sequence, view): for every
 // 128-slot tile of the sorted order the window of sorted slots its segments span, then the pad
@@ -22,6 +22,8 @@ namespace mate {
 
 constexpr int kSegThreads = 1024;
 constexpr int kSegWaves = kSegThreads / 64;
+constexpr int kDigitBits = 9;               // radix digit: ids below 512 sort in one pass
+constexpr unsigned kBins = 1u << kDigitBits;
 
 // Workgroup barrier for data exchanged through LDS only: waits for this wavefront's LDS traffic,
 // not for its global stores (a full fence would stall every phase on store round trips; nothing
@@ -54,11 +56,11 @@ __device__ inline int block_exclusive_scan(int v, int* tmp, int& total) {
   return base + inc - v;
 }
 
-// Lanes of the wavefront that hold the same 8-bit digit as this lane (valid lanes only).
+// Lanes of the wavefront that hold the same digit as this lane (valid lanes only).
 __device__ inline unsigned long long match_digit(unsigned digit, bool valid) {
   unsigned long long same = __ballot(valid);
 #pragma unroll
-  for (int bit = 0; bit < 8; ++bit) {
+  for (int bit = 0; bit < kDigitBits; ++bit) {
     const bool one = (digit >> bit) & 1u;
     const unsigned long long m = __ballot(one);
     same &= one ? m : ~m;
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   __shared__ int ids[P2];                  // id by token position; later: segment starts (ushort)
   __shared__ unsigned short buf_a[P2];     // current order of table-token positions
   __shared__ unsigned short buf_b[P2];     // next order; later: segment index by slot
-  __shared__ int hist[kSegWaves][256];     // per-wavefront digit counts -> running output slots
+  __shared__ unsigned short hist[kSegWaves][kBins];  // per-wavefront digit counts -> first output slots
   __shared__ int scan_tmp[kSegWaves + 1];
   __shared__ int wave_tot[3][kSegWaves];
   __shared__ int s_or, s_bad;
@@ -118,8 +120,8 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     if (i < N) {
       f = fl[i];
       if (f > 2) { bad = 1; f = 2; }
+      const int id = id_src[i];  // loaded for every position so that it does not wait for the flag
       if (f == 0) {
-        const int id = id_src[i];
         if (id < 0) bad = 1;
         ids[i] = id;
         my_or |= id;
@@ -177,48 +179,56 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   // ---- stable LSD radix sort of buf_a[0..L) by ids[position] --------------------------------
   unsigned short* cur = buf_a;
   unsigned short* nxt = buf_b;
-  const int w_hi = min(w0 + CHUNK, L);
-  for (int shift = 0; shift < 32; shift += 8) {
-    if (((all_bits >> shift) & 255u) == 0) continue;  // this digit is 0 everywhere: order unchanged
-    for (int i = tid; i < kSegWaves * 256; i += kSegThreads) (&hist[0][0])[i] = 0;
+  for (int shift = 0; shift < 32; shift += kDigitBits) {
+    if (((all_bits >> shift) & (kBins - 1u)) == 0) continue;  // digit 0 everywhere: order unchanged
+    for (int i = tid; i < kSegWaves * kBins / 2; i += kSegThreads) reinterpret_cast<int*>(&hist[0][0])[i] = 0;
     lds_barrier();
-    for (int s0 = w0; s0 < w_hi; s0 += 64) {
-      const int s = s0 + lane;
-      const bool valid = s < w_hi;
-      const unsigned digit = valid ? ((unsigned)ids[cur[s]] >> shift) & 255u : 0u;
-      const unsigned long long same = match_digit(digit, valid);
-      // one add per group of equal digits (neighbouring tokens mostly share a digit)
-      if (valid && (same & below) == 0) hist[wave][digit] += __popcll(same);
+    // count digits per wavefront; every element learns its rank among the equal digits of its
+    // wavefront's block (batches in order, lanes in order inside a batch)
+    int pos[NB], rank_w[NB];
+    unsigned dig[NB];
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const int s = w0 + e * 64 + lane;
+      pos[e] = s < L ? cur[s] : 0;
+      dig[e] = s < L ? ((unsigned)ids[pos[e]] >> shift) & (kBins - 1u) : 0u;
+    }
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const bool valid = w0 + e * 64 + lane < L;
+      const unsigned long long same = match_digit(dig[e], valid);
+      const int before = __popcll(same & below);
+      int old = 0;
+      if (valid && before == 0) {  // first lane of a group of equal digits
+        old = hist[wave][dig[e]];
+        hist[wave][dig[e]] = (unsigned short)(old + __popcll(same));
+      }
+      old = __shfl(old, valid ? __ffsll((long long)same) - 1 : lane, 64);
+      rank_w[e] = old + before;
     }
     lds_barrier();
     // counts -> first output slot of (digit, wavefront): digits ascending, wavefronts ascending
-    int tot = 0;
-    if (tid < 256) {
+    int first[kSegWaves], tot = 0;
+    if (tid < kBins) {
+#pragma unroll
+      for (int w = 0; w < kSegWaves; ++w) first[w] = hist[w][tid];
+#pragma unroll
       for (int w = 0; w < kSegWaves; ++w) {
-        const int c = hist[w][tid];
-        hist[w][tid] = tot;
+        const int c = first[w];
+        first[w] = tot;
         tot += c;
       }
     }
     int all;
     const int digit_base = block_exclusive_scan(tot, scan_tmp, all);
-    if (tid < 256)
-      for (int w = 0; w < kSegWaves; ++w) hist[w][tid] += digit_base;
-    lds_barrier();
-    // rank inside each 64-element batch in lane order; batches of a wavefront go in sequence
-    for (int s0 = w0; s0 < w_hi; s0 += 64) {
-      const int s = s0 + lane;
-      const bool valid = s < w_hi;
-      const unsigned pos = valid ? cur[s] : 0u;
-      const unsigned digit = valid ? ((unsigned)ids[pos] >> shift) & 255u : 0u;
-      const unsigned long long same = match_digit(digit, valid);
-      if (valid) {
-        const int rank = __popcll(same & below);
-        const int base = hist[wave][digit];
-        nxt[base + rank] = (unsigned short)pos;
-        if (rank == __popcll(same) - 1) hist[wave][digit] = base + __popcll(same);
-      }
+    if (tid < kBins) {
+#pragma unroll
+      for (int w = 0; w < kSegWaves; ++w) hist[w][tid] = (unsigned short)(first[w] + digit_base);
     }
+    lds_barrier();
+#pragma unroll
+    for (int e = 0; e < NB; ++e)
+      if (w0 + e * 64 + lane < L) nxt[hist[wave][dig[e]] + rank_w[e]] = (unsigned short)pos[e];
     lds_barrier();
     unsigned short* t = cur; cur = nxt; nxt = t;
   }
