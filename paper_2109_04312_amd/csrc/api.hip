@@ -66,7 +66,7 @@ size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bw
   if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS || D != MATE_HEAD_DIM) return 0;
   if (t == MATE_F32) return for_bwd ? delta_bytes(B, H, N) : 0;
   if (t != MATE_BF16) return 0;
-  return for_bwd ? delta_bytes(B, H, N) + 3 * part_bytes(B, H, N)
+  return for_bwd ? 2 * delta_bytes(B, H, N) + 3 * part_bytes(B, H, N)
                  : part_bytes(B, H, N) + stat_bytes(B, H, N);
 }
 
@@ -153,7 +153,8 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.delta = static_cast<float*>(workspace);
   if (t == MATE_BF16) {
-    char* p = static_cast<char*>(workspace) + delta_bytes(B, H, N);
+    a.nlse = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(B, H, N));
+    char* p = static_cast<char*>(workspace) + 2 * delta_bytes(B, H, N);
     for (int i = 0; i < 3; ++i) a.part[i] = reinterpret_cast<float*>(p + i * part_bytes(B, H, N));
   }
   hipStream_t s = static_cast<hipStream_t>(stream);

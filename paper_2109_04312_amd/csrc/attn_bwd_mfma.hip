@@ -74,8 +74,13 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   }
   delta = half_sum(delta);
   // every chunk of a question-token owner computes the same delta; the first one stores it
-  if (hl == 0 && me.valid && u.t_begin == 0) a.delta[bh + me.pos] = delta;
-  const float lse2 = a.lse[bh + me.pos] * kLog2e;
+  // (stored negated, with -lse / scale beside it: the dK/dV kernel starts its accumulators there)
+  const float lse = a.lse[bh + me.pos];
+  if (hl == 0 && me.valid && u.t_begin == 0) {
+    a.delta[bh + me.pos] = -delta;
+    a.nlse[bh + me.pos] = -lse / a.scale;
+  }
+  const float lse2 = lse * kLog2e;
   const float sc = a.scale * kLog2e;
 
   // K and V tiles stream through the LDS ring; K is read both plain (S^T = K Q^T) and
@@ -145,8 +150,10 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
     store_partial(dq_acc, a.scale, a.part[0] + slot * BM * kD, wave, lane);
     return;
   }
-  store_owned_rows(dq_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dQ, q_tok, wave, lane);
-  return;
+  const f32x16 (*accs[1])[2] = {&dq_acc};
+  const float muls[1] = {a.scale};
+  unsigned short* const outs[1] = {dQ};
+  store_owned_rows<1>(accs, muls, outs, lds, q_tok, wave, lane);
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
@@ -200,7 +207,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   // Q and dO tiles of the streamed queries go through the LDS ring, each read plain
   // (S = Q K^T, dP = dO V^T) and transposed (dK^T += Q^T dS, dV^T += dO^T P); wavefront 0
   // also brings the queries' lse, wavefront 1 their delta (one float per row).
-  const float* row_src = wave == 0 ? a.lse + bh : wave == 1 ? a.delta + bh : nullptr;
+  const float* row_src = wave == 0 ? a.nlse + bh : wave == 1 ? a.delta + bh : nullptr;
   TileStream<kDkvStage, kDkvNS> stream(u, global_idx, lds, idx_ring, Q, dO, row_src,
                                2 * kTileBytes + 256 * wave, wave, lane);
   stream.prologue();
@@ -233,27 +240,27 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
       // one 32-query block at a time, so only one block's scores are live
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib) {
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          s = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s);     // S  = Q K^T
-          dp = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp);   // dP = dO V^T
-        }
-        // rows of these tiles are the streamed queries: their lse / delta come from LDS, four
-        // consecutive rows per group of four registers
+        // Rows of these tiles are the streamed queries.  The accumulators start at the rows'
+        // -lse / scale and -delta (from LDS, four consecutive rows per group of four
+        // registers), so the contractions deliver S - lse / scale and dP - delta directly.
+        f32x16 s, dp;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int row0 = ib * 32 + 8 * g + 4 * hl;
           const float4 l4 = *reinterpret_cast<const float4*>(lse_row + row0);
           const float4 d4 = *reinterpret_cast<const float4*>(delta_row + row0);
-          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
+          s[4 * g] = l4.x; s[4 * g + 1] = l4.y; s[4 * g + 2] = l4.z; s[4 * g + 3] = l4.w;
+          dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
+        }
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int c = 4 * g + r;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[c], sc, -kLog2e * ls[r]));
-            s[c] = p;                       // P
-            dp[c] = p * (dp[c] - de[r]);    // dS
-          }
+        for (int ks = 0; ks < 4; ++ks) {
+          s = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s);     // S  = Q K^T
+          dp = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp);   // dP = dO V^T
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+          s[c] = __builtin_amdgcn_exp2f(s[c] * sc);  // P
+          dp[c] *= s[c];                             // dS
         }
         if (!full) {  // wave-uniform: zero the pairs outside the pattern
 #pragma unroll
@@ -285,9 +292,10 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     store_partial(dv_acc, 1.f, a.part[2] + slot * BM * kD, wave, lane);
     return;
   }
-  store_owned_rows(dk_acc, a.scale, reinterpret_cast<unsigned short*>(lds), dK, k_tok, wave, lane);
-  store_owned_rows(dv_acc, 1.f, reinterpret_cast<unsigned short*>(lds), dV, k_tok, wave, lane);
-  return;
+  const f32x16 (*accs[2])[2] = {&dk_acc, &dv_acc};
+  const float muls[2] = {a.scale, 1.f};
+  unsigned short* const outs[2] = {dK, dV};
+  store_owned_rows<2>(accs, muls, outs, lds, k_tok, wave, lane);
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {

@@ -158,7 +158,10 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
     return;
   }
   if (hl == 0 && me.valid) LSE[me.pos] = (m_run * sc + __builtin_amdgcn_logf(l_tot)) * kLn2;
-  store_owned_rows(o_acc, 1.f / l_tot, reinterpret_cast<unsigned short*>(lds), O, q_tok, wave, lane);
+  const f32x16 (*accs[1])[2] = {&o_acc};
+  const float muls[1] = {1.f / l_tot};
+  unsigned short* const outs[1] = {O};
+  store_owned_rows<1>(accs, muls, outs, lds, q_tok, wave, lane);
 }
 
 __global__ __launch_bounds__(kThreads, 4) void fwd_mfma_kernel(AttnArgs a) {

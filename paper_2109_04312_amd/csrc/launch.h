@@ -12,7 +12,8 @@ struct AttnArgs {
   void *out;                // forward only
   float* lse;               // forward: written; backward: read (const in spirit)
   void *dq, *dk, *dv;       // backward only
-  float* delta;             // backward scratch [B,H,N]
+  float* delta;             // backward scratch [B,H,N]: rowsum(dO * O), negated in the bf16 path
+  float* nlse;              // backward scratch [B,H,N] of the bf16 path: -lse / scale
   float* part[3];           // partial results of chunked question-token owners, per (b,h):
                             //   forward: [0] unnormalised O;  backward: dQ, dK, dV
   float* part_ml;           // forward: running max (log2 domain) and sum per partial row

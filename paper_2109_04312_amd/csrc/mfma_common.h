@@ -7,12 +7,6 @@
 // Every kernel here computes "transposed" score tiles (rows = keys or queries of the streamed
 // tile, columns = the rows the wavefront owns), so each lane owns one of the wavefront's rows
 // and per-row softmax statistics are per-lane scalars.
-//
-// Row permutation rho.  The 32 rows of a streamed tile are fed to the A operand permuted
-// (A row m' is tile row rho(m'), rho swaps bits 2 and 3), so that the eight C registers
-// c = 8*t .. 8*t+7 of a lane are the eight CONSECUTIVE tile rows 16*t + 8*hl + 0..7 -- which is
-// exactly the k-slice a lane must supply when those registers are fed back as the B operand of
-// the second contraction.  tile_row(c, hl) below is that map.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -23,16 +17,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kD = 64;             // head size
-constexpr int kLdsRow = kD + 8;    // LDS row pitch in bf16 elements (144 bytes: 16-byte aligned,
-                                   // and consecutive rows start 4 banks apart)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ inline int rho(int m) {  // swap bits 2 and 3 of a 5-bit row index
-  return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1);
-}
-// Tile row (0..31) held in C register c (0..15) of a lane in half hl.
-__device__ inline int tile_row(int c, int hl) { return 16 * (c >> 3) + 8 * hl + (c & 7); }
 
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -80,10 +66,6 @@ __device__ inline float sum8(bf16x8 p, float acc) {
   return acc;
 }
 
-__device__ inline bf16x8 lds_read8(const unsigned short* p) {
-  return *reinterpret_cast<const bf16x8*>(p);
-}
-
 __device__ inline bf16x8 as_bf16x8(uint4 v) {
   union { uint4 u; bf16x8 b; } x;
   x.u = v;
@@ -93,23 +75,6 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) {
 __device__ inline unsigned short f32_to_bf16_bits(float x) {
   __bf16 h = (__bf16)x;
   return __builtin_bit_cast(unsigned short, h);
-}
-
-// Four keys' rows (8 head dims each, r[j] = dims d0..d0+7 of key j) -> for each dim the four
-// keys packed as 8 bytes: the transposing step when a streamed tile is written to LDS as
-// [dim][key].
-__device__ inline uint2 transpose_pick(const uint4 r[4], int e) {
-  const unsigned w0 = (&r[0].x)[e >> 1], w1 = (&r[1].x)[e >> 1];
-  const unsigned w2 = (&r[2].x)[e >> 1], w3 = (&r[3].x)[e >> 1];
-  uint2 o;
-  if (e & 1) {
-    o.x = (w0 >> 16) | (w1 & 0xffff0000u);
-    o.y = (w2 >> 16) | (w3 & 0xffff0000u);
-  } else {
-    o.x = (w0 & 0xffffu) | (w1 << 16);
-    o.y = (w2 & 0xffffu) | (w3 << 16);
-  }
-  return o;
 }
 
 }  // namespace mate

@@ -161,33 +161,40 @@ __device__ inline OwnedRow owned_row(const UnitPlan& u, const AttnArgs& a, int b
   return r;
 }
 
-// Final results: a C tile pair (columns = owned rows, registers = head dims) scaled, rounded to
-// bf16, transposed through LDS and stored as whole 128-byte token rows.  Two barriers.
-__device__ inline void store_owned_rows(const f32x16 acc[2], float mul, unsigned short* stage,
-                                        unsigned short* __restrict__ out, const int* row_tok,
-                                        int wave, int lane) {
+// Final results: C tile pairs (columns = owned rows, registers = head dims) scaled, rounded to
+// bf16, transposed through LDS and stored as whole 128-byte token rows.  `stage` needs 16 KB per
+// tensor: 128 rows of 128 bytes whose 16-byte chunks are XOR-swizzled with the row number so
+// that both the column-wise writes and the row-wise reads spread over all banks.  One barrier;
+// the staging area must not be reused by the caller afterwards without another one.
+template <int kTensors>
+__device__ inline void store_owned_rows(const f32x16 (*acc[kTensors])[2], const float (&mul)[kTensors],
+                                        unsigned short* const (&out)[kTensors], char* stage,
+                                        const int* row_tok, int wave, int lane) {
   const int m = lane & 31, hl = lane >> 5;
+  const int wrow = wave * 32 + m;
 #pragma unroll
-  for (int db = 0; db < 2; ++db)
+  for (int x = 0; x < kTensors; ++x)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint2 w;
-      w.x = f32_to_bf16_bits(acc[db][4 * g] * mul) |
-            ((unsigned)f32_to_bf16_bits(acc[db][4 * g + 1] * mul) << 16);
-      w.y = f32_to_bf16_bits(acc[db][4 * g + 2] * mul) |
-            ((unsigned)f32_to_bf16_bits(acc[db][4 * g + 3] * mul) << 16);
-      *reinterpret_cast<uint2*>(stage + (wave * 32 + m) * kLdsRow + db * 32 + 8 * g + 4 * hl) = w;
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x16& a = (*acc[x])[db];
+        uint2 w;
+        w.x = f32_to_bf16_bits(a[4 * g] * mul[x]) | ((unsigned)f32_to_bf16_bits(a[4 * g + 1] * mul[x]) << 16);
+        w.y = f32_to_bf16_bits(a[4 * g + 2] * mul[x]) | ((unsigned)f32_to_bf16_bits(a[4 * g + 3] * mul[x]) << 16);
+        *reinterpret_cast<uint2*>(stage + x * (BM * 128) + wrow * 128 + (((4 * db + g) ^ (wrow & 7)) << 4) + 8 * hl) = w;
+      }
+  __syncthreads();
+#pragma unroll
+  for (int x = 0; x < kTensors; ++x)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = wave * 32 + it * 8 + (lane >> 3), piece = lane & 7;
+      const int tok = row_tok[row];
+      if (tok >= 0)
+        *reinterpret_cast<uint4*>(out[x] + (size_t)tok * kD + piece * 8) =
+            *reinterpret_cast<const uint4*>(stage + x * (BM * 128) + row * 128 + ((piece ^ (row & 7)) << 4));
     }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = wave * 32 + it * 8 + (lane >> 3), piece = lane & 7;
-    const int tok = row_tok[row];
-    if (tok >= 0)
-      *reinterpret_cast<uint4*>(out + (size_t)tok * kD + piece * 8) =
-          *reinterpret_cast<const uint4*>(stage + row * kLdsRow + piece * 8);
-  }
-  __syncthreads();
 }
 
 // Partial results of a chunked question-token owner: fp32 [128][64], row = owned row.
