@@ -24,6 +24,7 @@ namespace mate {
 namespace {
 
 constexpr int kStageBytes = 2 * kTileBytes;   // K tile, V tile
+constexpr float kLazyBits = 8.f;
 constexpr int NS = 2;  // LDS stages: small enough for four workgroups per CU
 
 __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
@@ -61,6 +62,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
     qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(Q + (size_t)me.pos * kD + ks * 16 + hl * 8));
 
   const float sc = a.scale * kLog2e;  // scores are kept raw; exp2(s * sc - m * sc)
+  const float lazy = kLazyBits / sc;   // in raw-score units
   f32x16 o_acc[2] = {zero16(), zero16()};
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
@@ -112,11 +114,16 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
             s[jb][c] = in ? s[jb][c] : -INFINITY;
           }
       }
-      float mx = fmaxf(s[0][0], s[1][0]);
+      float mx = s[0][0];
 #pragma unroll
-      for (int c = 1; c < 16; ++c) mx = fmaxf(mx, fmaxf(s[0][c], s[1][c]));
+      for (int c = 1; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[0][c]), s[0][c + 1 < 16 ? c + 1 : 0]);
+#pragma unroll
+      for (int c = 0; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[1][c]), s[1][c + 1]);
       mx = half_max(mx);
-      if (__any(mx > m_run)) {  // rescale only when some row's maximum moved
+      // Rescale only when some row's maximum has moved up by more than 2^kLazyBits in the exponent
+      // domain.  Until then probabilities may exceed 1 by that factor, which changes neither
+      // their relative rounding in bf16 nor the fp32 sums' accuracy.
+      if (__any(mx > m_run + lazy)) {
         const float m_new = fmaxf(m_run, mx);
         const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * sc);
         l_run *= alpha;

@@ -51,27 +51,35 @@ __device__ inline unsigned lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane(
       (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p);
 }
-__device__ inline void load_to_lds_16(const void* g, const void* lds_dst /* wave-uniform */) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(g), "s"(lds_addr(lds_dst)) : "memory", "m0");
+// Address form: 64-bit base in scalar registers (wave-uniform) plus a 32-bit byte offset per
+// lane, so the per-lane address arithmetic is one shift-add.
+__device__ inline void load_to_lds_16(const void* base /* wave-uniform */, unsigned byte_off,
+                                      const void* lds_dst /* wave-uniform */) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(byte_off), "s"(base), "s"(lds_addr(lds_dst)) : "memory", "m0");
 }
-__device__ inline void load_to_lds_4(const void* g, const void* lds_dst /* wave-uniform */) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               :: "v"(g), "s"(lds_addr(lds_dst)) : "memory", "m0");
+__device__ inline void load_to_lds_4(const void* base /* wave-uniform */, unsigned byte_off,
+                                     const void* lds_dst /* wave-uniform */) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(byte_off), "s"(base), "s"(lds_addr(lds_dst)) : "memory", "m0");
 }
 
-// Rows `tok0` / `tok1` (token positions of this lane's two rows) of tensor X into the tile at
-// LDS address `tile` (wave-uniform).
-__device__ inline void issue_tile(const unsigned short* __restrict__ X, int tok0, int tok1,
+// Rows `tok0` / `tok1` (token positions of this lane's two rows) of tensor X (wave-uniform
+// base; a (sequence, head) slice, so byte offsets fit 32 bits) into the tile at LDS address
+// `tile` (wave-uniform).
+__device__ inline void issue_tile(const unsigned short* X, int tok0, int tok1,
                                   const LoadLane& l, const char* tile, int wave) {
   const char* d0 = tile + (16 * wave) * 128;
-  load_to_lds_16(X + (size_t)tok0 * kD + l.chunk0 * 8, d0);
-  load_to_lds_16(X + (size_t)tok1 * kD + (l.chunk0 ^ 2) * 8, d0 + 8 * 128);
+  load_to_lds_16(X, (unsigned)tok0 * 128u + l.chunk0 * 16, d0);
+  load_to_lds_16(X, (unsigned)tok1 * 128u + (l.chunk0 ^ 2) * 16, d0 + 8 * 128);
 }
 
-// One 32-bit word per lane from `src` (per-lane address) to 64 consecutive words at `dst`
-// (wave-uniform LDS address): token indices, or per-row statistics, of a streamed tile.
-__device__ inline void issue_row_words(const void* src, const void* dst) { load_to_lds_4(src, dst); }
+// One 32-bit word per lane, word `index` of the array at `base` (wave-uniform), to 64
+// consecutive words at `dst` (wave-uniform LDS address): token indices, or per-row statistics,
+// of a streamed tile.
+__device__ inline void issue_row_words(const void* base, int index, const void* dst) {
+  load_to_lds_4(base, (unsigned)index * 4u, dst);
+}
 
 // ---- waiting ------------------------------------------------------------------------------
 // "At most n of my vector-memory loads still outstanding" (n wave-uniform).  Loads complete in

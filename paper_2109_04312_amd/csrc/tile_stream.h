@@ -52,7 +52,7 @@ struct TileStream {
     const int* list; int base, last;
     if (wave != (t & 3)) return;
     tile_source(u, global_idx, t, list, base, last);
-    issue_row_words(list + min(base + lane, last), &ring[t & (kIdxSlots - 1)][0]);
+    issue_row_words(list, min(base + lane, last), &ring[t & (kIdxSlots - 1)][0]);
     note(1);
   }
   __device__ void issue_data(int t, int k /* = t - current tile */) {
@@ -63,7 +63,7 @@ struct TileStream {
     issue_tile(X1, x0, x1, ll, st + kTileBytes, wave);
     note(4);
     if (row_src) {
-      issue_row_words(row_src + r[lane], st + row_off);
+      issue_row_words(row_src, r[lane], st + row_off);
       note(1);
     }
     since[k] = 0;
