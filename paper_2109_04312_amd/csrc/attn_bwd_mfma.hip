@@ -57,38 +57,45 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
     zero_pad_rows(dQ, u, tid);
     return;
   }
+  // First round trip: which rows this workgroup owns, and the token indices of the first tiles.
+  // Second: the owned rows (registers) and the first K / V tiles (LDS), all in flight together.
+  // K and V tiles stream through the LDS ring; K is read both plain (S^T = K Q^T) and
+  // transposed (dQ^T += K^T dS^T), V plain (dP^T = V dO^T).
+  TileStream<kDqStage, kDqNS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
+  stream.begin();
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
   if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  stream.prime();
 
   // this lane's query row and dO row as B operands (column m, k = dims), and delta
-  bf16x8 qf[4], gf[4];
-  float delta = 0.f;
+  bf16x8 qf[4], gf[4], of[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
     const size_t off = (size_t)me.pos * kD + ks * 16 + hl * 8;
     qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(Q + off));
     gf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(dO + off));
-    const bf16x8 of = as_bf16x8(*reinterpret_cast<const uint4*>(O + off));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) delta = fmaf((float)gf[ks][e], (float)of[e], delta);
+    of[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(O + off));
   }
+  const float lse = a.lse[bh + me.pos];
+  // Everything loaded into registers so far is pinned as complete here, so that no load with a
+  // register destination is pending inside the loop.
+  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(gf[0]), "v"(gf[1]),
+               "v"(gf[2]), "v"(gf[3]), "v"(of[0]), "v"(of[1]), "v"(of[2]), "v"(of[3]), "v"(lse));
+  float delta = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) delta = fmaf((float)gf[ks][e], (float)of[ks][e], delta);
   delta = half_sum(delta);
   // every chunk of a question-token owner computes the same delta; the first one stores it
   // (stored negated, with -lse / scale beside it: the dK/dV kernel starts its accumulators there)
-  const float lse = a.lse[bh + me.pos];
   if (hl == 0 && me.valid && u.t_begin == 0) {
     a.delta[bh + me.pos] = -delta;
     a.nlse[bh + me.pos] = -lse / a.scale;
   }
   const float lse2 = lse * kLog2e;
   const float sc = a.scale * kLog2e;
-
-  // K and V tiles stream through the LDS ring; K is read both plain (S^T = K Q^T) and
-  // transposed (dQ^T += K^T dS^T), V plain (dP^T = V dO^T).
-  TileStream<kDqStage, kDqNS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
-  stream.prologue();
-  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(gf[0]), "v"(gf[1]),
-               "v"(gf[2]), "v"(gf[3]), "v"(me.lo), "v"(me.hi), "v"(lse2), "v"(delta));
 
   int koff[4], toff[2][2];
 #pragma unroll
@@ -191,9 +198,20 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     zero_pad_rows(dV, u, tid);
     return;
   }
+  // Q and dO tiles of the streamed queries go through the LDS ring, each read plain
+  // (S = Q K^T, dP = dO V^T) and transposed (dK^T += Q^T dS, dV^T += dO^T P); wavefront 0
+  // also brings the queries' -lse / scale, wavefront 1 their -delta (one float per row).
+  // First round trip: the owned rows' positions and the first tiles' token indices; second:
+  // the owned K / V rows (registers) and the first tiles (LDS).
+  const float* row_src = wave == 0 ? a.nlse + bh : wave == 1 ? a.delta + bh : nullptr;
+  TileStream<kDkvStage, kDkvNS> stream(u, global_idx, lds, idx_ring, Q, dO, row_src,
+                               2 * kTileBytes + 256 * wave, wave, lane);
+  stream.begin();
   // `me` is this lane's key; its window is the set of query slots that see it
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
   if (tid < BM) k_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  stream.prime();
 
   bf16x8 kf[4], vf[4];  // this lane's key and value rows as B operands
 #pragma unroll
@@ -203,16 +221,8 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     vf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(V + off));
   }
   const float sc = a.scale * kLog2e;
-
-  // Q and dO tiles of the streamed queries go through the LDS ring, each read plain
-  // (S = Q K^T, dP = dO V^T) and transposed (dK^T += Q^T dS, dV^T += dO^T P); wavefront 0
-  // also brings the queries' lse, wavefront 1 their delta (one float per row).
-  const float* row_src = wave == 0 ? a.nlse + bh : wave == 1 ? a.delta + bh : nullptr;
-  TileStream<kDkvStage, kDkvNS> stream(u, global_idx, lds, idx_ring, Q, dO, row_src,
-                               2 * kTileBytes + 256 * wave, wave, lane);
-  stream.prologue();
   asm volatile("" ::"v"(kf[0]), "v"(kf[1]), "v"(kf[2]), "v"(kf[3]), "v"(vf[0]), "v"(vf[1]),
-               "v"(vf[2]), "v"(vf[3]), "v"(me.lo), "v"(me.hi));
+               "v"(vf[2]), "v"(vf[3]));
 
   int poff[4], toff[2][2];
 #pragma unroll

@@ -53,8 +53,15 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
     return;
   }
 
+  // First round trip: which rows this workgroup owns, and the token indices of the first tiles.
+  // Second: the owned query rows (registers) and the first K / V tiles (LDS), all in flight
+  // together.
+  TileStream<kStageBytes, NS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
+  stream.begin();
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
   if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  stream.prime();
 
   bf16x8 qf[4];
 #pragma unroll
@@ -66,14 +73,11 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   f32x16 o_acc[2] = {zero16(), zero16()};
   float m_run = -INFINITY, l_run = 0.f;  // running max of raw scores; this lane-half's share of the sum
 
-  // ---- streaming: K and V tiles go straight from global memory into a ring of LDS stages
-  TileStream<kStageBytes, NS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
-  stream.prologue();
   const int tb = u.t_begin, te = u.t_end;
   // Everything loaded into registers so far is pinned as complete here, so that no load with a
   // register destination is pending inside the loop (the compiler would otherwise wait for
   // *all* outstanding loads, prefetches included, at the first use).
-  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(me.lo), "v"(me.hi));
+  asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]));
 
   int koff[4], voff[2][2];
 #pragma unroll

@@ -68,11 +68,16 @@ struct TileStream {
     }
     since[k] = 0;
   }
-  // Before the loop: indices of the first 2 NS - 2 tiles, then data of the first NS - 1.
-  __device__ void prologue() {
+  // Before the loop, in two steps so that the caller's own first loads (which rows it owns) can
+  // travel together with the first index loads, and its row loads together with the first tiles:
+  // begin() issues the indices of the first 2 NS - 2 tiles; prime() waits for them and issues the
+  // data of the first NS - 1 tiles.
+  __device__ void begin() {
 #pragma unroll
     for (int s = 0; s < 2 * NS - 2; ++s)
       if (u.t_begin + s < u.t_end) issue_idx(u.t_begin + s);
+  }
+  __device__ void prime() {
     wait_vmcnt_le(0);
     barrier_no_fence();  // every wavefront's share of the first indices is in the ring
 #pragma unroll
