@@ -49,7 +49,8 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
 
   if (u.kind == UNIT_PAD) {  // pad positions: O = 0, LSE = 0
     zero_pad_rows(O, u, tid);
-    if (tid < BM && u.t0 + tid < u.own_count) LSE[u.own_list[u.t0 + tid]] = 0.f;
+    for (int x = tid; x < kPadSlots; x += kThreads)
+      if (u.t0 + x < u.own_count) LSE[u.own_list[u.t0 + x]] = 0.f;
     return;
   }
 

@@ -12,7 +12,8 @@
 //     seg_of_tok[B][N]   token position -> segment index, -1 for GLOBAL / PAD
 //     slot_rng[B][N][2]  per sorted slot: [first slot, one-past-last slot) of its segment
 //     unit[B][T + 2][8]  work units of table-token owners (one per 128-slot tile of the sorted
-//                        order), then of pad owners, then empty records
+//                        order), then of pad owners (1024 pad positions each), then empty
+//                        records
 //
 // A work unit is what one workgroup of the bf16 attention kernels does: it owns up to 128 rows
 // and streams 64-row tiles of the other side.  Record (8 words):
@@ -34,6 +35,7 @@ constexpr int kCountWords = 12;
 enum { C_G = 0, C_L = 1, C_P = 2, C_SROW = 3, C_SCOL = 4 };
 constexpr int kTileSlots = 128;    // sorted slots per tile (= rows owned by one workgroup)
 constexpr int kMaxTiles = 128;     // MATE_MAX_N / kTileSlots
+constexpr int kPadSlots = 1024;    // pad positions zero-filled by one pad unit
 constexpr int kUnitWords = 8;
 constexpr int BM = kTileSlots;     // owned rows per workgroup (32 per wavefront)
 constexpr int BN = 64;             // streamed rows per tile

@@ -290,7 +290,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   // ---- work units of the attention kernels -------------------------------------------------
   // table-token owners: 128 sorted slots each, streaming the question tokens and then the slot
   // window spanned by the segments those slots touch; pad owners after them
-  const int n_lt = (L + kTileSlots - 1) / kTileSlots, n_pt = (P + kTileSlots - 1) / kTileSlots;
+  const int n_lt = (L + kTileSlots - 1) / kTileSlots, n_pt = (P + kPadSlots - 1) / kPadSlots;
   const int n_t0 = (G + BN - 1) / BN;
   if (tid < lay.tiles + 2) {
     int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
       r0 = make_int4(UNIT_LOCAL, t0, lo, hi);
       r1.y = n_t0 + (hi - lo + BN - 1) / BN;
     } else if (tid < n_lt + n_pt) {
-      r0 = make_int4(UNIT_PAD, (tid - n_lt) * kTileSlots, 0, 0);
+      r0 = make_int4(UNIT_PAD, (tid - n_lt) * kPadSlots, 0, 0);
     }
     unit[2 * tid] = r0;
     unit[2 * tid + 1] = r1;

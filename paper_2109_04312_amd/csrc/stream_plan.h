@@ -8,7 +8,7 @@
 // Units of one (sequence, head) -- listed by the segment builder, see seg_layout.h:
 //   local   ceil(L / 128) table-token owners, 128 consecutive slots of the head kind's sorted
 //           order
-//   pad     ceil(P / 128) pad owners (zero fill)
+//   pad     ceil(P / 1024) pad owners (zero fill)
 //   global  question-token owners.  Their streamed side is the whole sequence, so it is cut into
 //           chunks that run as separate units and leave partial results, merged by a finalize
 //           kernel.
@@ -18,8 +18,10 @@
 // share an L2).  Column-head pairs are numbered c = b n_col + i and belong to queue c mod 8, row-
 // head pairs r = b n_row + i to queue r mod 8.  Order inside a queue, longest units first:
 //   1. column heads: table-token (then pad) tile 0 of every pair, tile 1 of every pair, ...
-//   2. question-token units of all pairs, the same way
+//   2. the first quarter of the question-token unit records of all pairs, the same way (all
+//      of the real ones unless most of the sequence is question tokens)
 //   3. row heads, as in 1
+//   4. the remaining question-token unit records
 // Records of kind "none" pad every pair to the same count; their workgroups exit at once.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -62,29 +64,38 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   const int T = a.seg.tiles, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
   const int q = blockIdx.x & 7;
   const int nc = (a.B * n_col - q + 7) >> 3, nr = (a.B * n_row - q + 7) >> 3;  // pairs of this queue
+  const int T1 = (T + 3) >> 2;  // question-token units per pair in the early part of their list
   int t = blockIdx.x >> 3;
-  // region -> (first pair, pairs, records per pair)
-  int first = 0, pairs = nc, per = T + 2;
+  // region -> (first pair, pairs, first record, records per pair)
+  int first = 0, pairs = nc, k0 = 0, per = T + 2;
   bool glob = false;
   if (t >= nc * (T + 2)) {
     t -= nc * (T + 2);
     pairs = nc + nr;
-    per = T;
+    per = T1;
     glob = true;
-    if (t >= pairs * T) {
-      t -= pairs * T;
+    if (t >= pairs * T1) {
+      t -= pairs * T1;
       first = nc;
       pairs = nr;
       per = T + 2;
       glob = false;
+      if (t >= nr * (T + 2)) {
+        t -= nr * (T + 2);
+        first = 0;
+        pairs = nc + nr;
+        k0 = T1;
+        per = T - T1;
+        glob = true;
+      }
     }
   }
   if (pairs <= 0) return false;
   // The hardware hands consecutive workgroups of an XCD to its shader engines in rotation and
   // stalls when the engine whose turn it is has no room, so each engine must see the same mix
   // of units: the pair order rotates from sweep to sweep.
-  const int k = t / pairs, j = first + (t + k) % pairs;
-  if (k >= per) return false;
+  const int kk = t / pairs, j = first + (t + kk) % pairs, k = k0 + kk;
+  if (kk >= per) return false;
   int b, h;
   if (j < nc) {
     const int c = q + 8 * j;
@@ -212,7 +223,7 @@ __device__ inline void store_partial(const f32x16 acc[2], float mul, float* __re
 }
 
 __device__ inline void zero_pad_rows(unsigned short* __restrict__ out, const UnitPlan& u, int tid) {
-  for (int x = tid; x < BM * 8; x += kThreads) {
+  for (int x = tid; x < kPadSlots * 8; x += kThreads) {
     const int row = x >> 3, piece = x & 7;
     if (u.t0 + row < u.own_count)
       *reinterpret_cast<uint4*>(out + (size_t)u.own_list[u.t0 + row] * kD + piece * 8) =
