@@ -327,26 +327,27 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
   for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
   const int gt = x / BM, r = x % BM;
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
-  // chunks are read four at a time so that their loads overlap; the order of the additions
+  // chunks are read sixteen at a time so that their loads overlap; the order of the additions
   // is fixed, so the result is deterministic
+  const int tok = a.seg.global_idx[(size_t)b * N + x];
+  constexpr int kBatch = 16;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int c0 = 0; c0 < s.n_chunks; c0 += 4) {
-    float4 p0[4], p1[4];
+  for (int c0 = 0; c0 < s.n_chunks; c0 += kBatch) {
+    float4 p0[kBatch], p1[kBatch];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < kBatch; ++e) {
       const int c = min(c0 + e, s.n_chunks - 1);
       const float* p = a.part[which] + ((slot0 + c) * BM + r) * kD + piece * 8;
       p0[e] = *reinterpret_cast<const float4*>(p);
       p1[e] = *reinterpret_cast<const float4*>(p + 4);
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < kBatch; ++e) {
       const float w = c0 + e < s.n_chunks ? 1.f : 0.f;
       acc[0] += w * p0[e].x; acc[1] += w * p0[e].y; acc[2] += w * p0[e].z; acc[3] += w * p0[e].w;
       acc[4] += w * p1[e].x; acc[5] += w * p1[e].y; acc[6] += w * p1[e].z; acc[7] += w * p1[e].w;
     }
   }
-  const int tok = a.seg.global_idx[(size_t)b * N + x];
   void* dst = which == 0 ? a.dq : which == 1 ? a.dk : a.dv;
   uint4 w;
   w.x = f32_to_bf16_bits(acc[0]) | ((unsigned)f32_to_bf16_bits(acc[1]) << 16);

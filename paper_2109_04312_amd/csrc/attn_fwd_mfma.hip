@@ -194,11 +194,29 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
   const int piece = threadIdx.x & 7;
   for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
   const int gt = x / BM, r = x % BM;
+  const int tok = a.seg.global_idx[(size_t)b * N + x];
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
-  // chunks are read several at a time so that their loads overlap (the chunk count is only
-  // known on the device); the combination order is fixed, so the result is deterministic
+  // Chunks are read kBatch at a time so that their loads overlap (the chunk count is only known
+  // on the device); the combination order is fixed, so the result is deterministic.  A first
+  // batch usually covers every chunk: then each partial is read exactly once.
+  constexpr int kBatch = 16;
   float m = -INFINITY;
-  for (int c0 = 0; c0 < s.n_chunks; c0 += 8) {
+  float2 ml[kBatch];
+  float4 p0[kBatch], p1[kBatch];
+  auto load_batch = [&](int c0) {
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int c = min(c0 + e, s.n_chunks - 1);
+      ml[e] = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
+      const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
+      p0[e] = *reinterpret_cast<const float4*>(p);
+      p1[e] = *reinterpret_cast<const float4*>(p + 4);
+    }
+  };
+  load_batch(0);
+#pragma unroll
+  for (int e = 0; e < kBatch; ++e) m = fmaxf(m, e < s.n_chunks ? ml[e].x : -INFINITY);
+  for (int c0 = kBatch; c0 < s.n_chunks; c0 += 8) {  // more chunks than one batch: finish the maximum first
     float mv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e)
@@ -207,19 +225,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
     for (int e = 0; e < 8; ++e) m = fmaxf(m, mv[e]);
   }
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, l = 0.f;
-  for (int c0 = 0; c0 < s.n_chunks; c0 += 4) {
-    float2 ml[4];
-    float4 p0[4], p1[4];
+  for (int c0 = 0; c0 < s.n_chunks; c0 += kBatch) {
+    if (c0) load_batch(c0);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int c = min(c0 + e, s.n_chunks - 1);
-      ml[e] = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
-      const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
-      p0[e] = *reinterpret_cast<const float4*>(p);
-      p1[e] = *reinterpret_cast<const float4*>(p + 4);
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < kBatch; ++e) {
       const float w = c0 + e < s.n_chunks ? __builtin_amdgcn_exp2f(ml[e].x - m) : 0.f;
       l += w * ml[e].y;
       acc[0] += w * p0[e].x; acc[1] += w * p0[e].y; acc[2] += w * p0[e].z; acc[3] += w * p0[e].w;
@@ -227,7 +236,6 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
     }
   }
   const float inv = 1.f / l;
-  const int tok = a.seg.global_idx[(size_t)b * N + x];
   const size_t bh = (size_t)bh_i * N;
   uint4 w;
   w.x = f32_to_bf16_bits(acc[0] * inv) | ((unsigned)f32_to_bf16_bits(acc[1] * inv) << 16);

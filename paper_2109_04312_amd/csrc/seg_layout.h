@@ -39,7 +39,7 @@ constexpr int kPadSlots = 1024;    // pad positions zero-filled by one pad unit
 constexpr int kUnitWords = 8;
 constexpr int BM = kTileSlots;     // owned rows per workgroup (32 per wavefront)
 constexpr int BN = 64;             // streamed rows per tile
-constexpr int kMinChunkTiles = 8;  // streamed tiles per chunk of a question-token owner
+constexpr int kMinChunkTiles = 16; // streamed tiles per chunk of a question-token owner
 enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
 
 __host__ __device__ inline int owner_slots(int N) { return (N + BM - 1) / BM; }  // T
