@@ -180,6 +180,11 @@ def main():
             "bwd_dkv_mfma_kernel": (4 * D * pairs, t_dkv)}
     dom = max(cand, key=lambda n: cand[n][1])
     ach = cand[dom][0] / cand[dom][1] / 1e12
+    # the same kernel against the HBM roof: tensor passes it would need as a stand-alone kernel
+    # (128 B per non-pad token row per head per pass)
+    passes = {"fwd_mfma_kernel": 4, "bwd_dq_mfma_kernel": 6, "bwd_dkv_mfma_kernel": 6}[dom]
+    alg_bytes = passes * 128 * nonpad * H
+    hbm_gbs = alg_bytes / cand[dom][1] / 1e9
     t_attn = ms_per_step * 1e-3 - t_build
     traffic = TRAFFIC.get(w.name, {}).get(dom)
     traffic_detail = None
@@ -205,7 +210,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "algorithmic_flop_per_launch": cand[dom][0],
-                     "avg_launch_us": cand[dom][1] * 1e6},
+                     "avg_launch_us": cand[dom][1] * 1e6,
+                     "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved": hbm_gbs,
+                                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS}},
         "segment_builder": {"us": t_build * 1e6, "keys_per_s": 2 * tokens / t_build,
                             "algorithmic_GBps": 30.0 * tokens / t_build / 1e9,
                             "frac_hbm": 30.0 * tokens / t_build / 1e9 / PEAK_HBM_GBS},
