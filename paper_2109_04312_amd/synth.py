@@ -131,11 +131,12 @@ CONFIG_NAMES = {
     3: "cfg3_B8_N2048_H16",
     4: "cfg4_B2_N8192_H16",
     5: "cfg5_ragged_B16_N4096_H16",
+    6: "cfg6_longcells_B8_N2048_H16",
 }
 
 
 def config_structure(idx: int, rng: np.random.Generator):
-    """Structure + (B,N,H,D,dtype,backward?) of benchmark configuration `idx` (1..5)."""
+    """Structure + (B,N,H,D,dtype,backward?) of benchmark configuration `idx` (1..6)."""
     D = 64
     if idx == 1:
         B, N, H, dtype, bwd = 1, 128, 4, "f32", False
@@ -165,13 +166,25 @@ def config_structure(idx: int, rng: np.random.Generator):
             if b == 1:
                 C = 1      # degenerate one-column table
             seqs.append(flatten_table(N, G, R, C, geometric_lengths(rng, 3.0, 16, R * C)))
+    elif idx == 6:
+        # Long expanded cells (the shape of the paper's HybridQA inputs, Section 4 and the
+        # appendix on hyper-parameters: about 70 cells, most of them with tens of tokens of
+        # entity text, sequence length 2048): rows AND columns are segments of hundreds of tokens.
+        B, N, H, dtype, bwd = 8, 2048, 16, "bf16", True
+        seqs = []
+        for _ in range(B):
+            R, C = 14, 5
+            long_cell = rng.random(R * C) < 0.63
+            lens = np.where(long_cell, geometric_lengths(rng, 40.0, 120, R * C),
+                            geometric_lengths(rng, 2.0, 8, R * C))
+            seqs.append(flatten_table(N, 64, R, C, lens))
     else:
         raise ValueError(f"unknown config {idx}")
     return _stack(seqs), (B, N, H, D, dtype, bwd)
 
 
 def make_config(idx: int, seed: Optional[int] = None, tensors: bool = True) -> Workload:
-    """Benchmark configuration `idx` (1..5); seed defaults to BASE_SEED + idx."""
+    """Benchmark configuration `idx` (1..6); seed defaults to BASE_SEED + idx."""
     rng = np.random.default_rng(BASE_SEED + idx if seed is None else seed)
     st, (B, N, H, D, dtype, bwd) = config_structure(idx, rng)
     hk = half_row_half_col(H)

@@ -102,6 +102,12 @@ def test_config5_ragged_sampled_heads():
     check_workload(w, backward=True, pairs=[(0, 0), (0, 8), (1, 3), (1, 12), (9, 1), (15, 14)])
 
 
+def test_config6_long_cells_sampled_heads():
+    # long expanded cells: both views have segments of hundreds of tokens
+    w = synth.make_config(6)
+    check_workload(w, backward=True, pairs=[(0, 0), (0, 8), (3, 5), (7, 15)])
+
+
 def test_backward_is_bit_reproducible():
     from paper_2109_04312_amd import mate
     w = small_workload(5, "bf16", B=2, N=700, H=4, max_rows=40, max_cols=6, max_global=70, max_cell=5)

@@ -15,7 +15,7 @@ def _build(st):
     return mate.build_segments(r, c, f)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 def test_segments_benchmark_configs(idx):
     print(f"segments config {idx}", flush=True)
     w = synth.make_config(idx, tensors=False)
