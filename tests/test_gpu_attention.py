@@ -79,6 +79,20 @@ def test_many_question_tokens(n_global, N):
     check_workload(w, backward=True)
 
 
+def test_maximum_sequence_length():
+    """N = 16384, the largest length the library accepts (the segment builder's LDS limit): a
+    full 128-tile owner grid, 9-bit and 10-bit ids, a sequence filled to the last position."""
+    N = 16384
+    rng = np.random.default_rng(16384)
+    R, C = 700, 12
+    row, col, flag = synth.flatten_table(N, 100, R, C, synth.geometric_lengths(rng, 2.0, 8, R * C))
+    assert (flag != synth.TOK_PAD).all()      # the table is cut at N: no padding at all
+    st = synth.Structure(row[None], col[None], flag[None])
+    q, k, v, do = synth.draw_tensors(rng, 1, 2, N, 64, "bf16", 4)
+    w = synth.Workload("max_length", "bf16", st, np.array([ROW, COL], np.uint8), q, k, v, do, 0.125)
+    check_workload(w, backward=True)
+
+
 def test_config2_bf16_fwd_bwd():
     check_workload(synth.make_config(2), backward=True)
 
