@@ -5,7 +5,8 @@
 //   dq kernel  -- a workgroup owns 128 queries (sorted order of the head kind, or question
 //                 tokens) and streams the key tiles they see, exactly like the forward:
 //                 P = exp(S - LSE), dP = dO V^T, dS = P (dP - delta), dQ += dS K.
-//                 It also produces delta_k = dO_k . O_k for its queries.
+//                 It also produces delta_k = dO_k . O_k for its queries and leaves -delta and
+//                 -LSE / scale for the next kernel.
 //   dkv kernel -- a workgroup owns 128 keys and streams the query tiles that see them: the
 //                 question tokens plus the table tokens of the keys' own segments (every
 //                 non-pad token when the keys are question tokens):
@@ -30,7 +31,7 @@ namespace {
 // ======================================================================================
 constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
 constexpr int kDqNS = 3, kDkvNS = 2;              // LDS stages of the two kernels
-constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, lse[64], delta[64]
+constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, -lse/scale[64], -delta[64]
 
 __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   __shared__ __attribute__((aligned(1024))) char lds[kDqNS * kDqStage];

@@ -2,13 +2,14 @@
 // Section 3.1: per-head-kind ordering so that a token's keys are contiguous).
 //
 // A workgroup (4 wavefronts) owns 128 consecutive queries of one (sequence, head) in the head
-// kind's sorted order -- or 128 question tokens, or 128 pad tokens (zero fill).  It streams the
+// kind's sorted order -- or 128 question tokens, or 1024 pad tokens (zero fill).  It streams the
 // keys those queries may see in 64-key tiles: first the question tokens (gathered through
 // global_idx), then the sorted slots spanned by the queries' own row / column segments
 // (gathered through perm; every table token for question-token owners, whose key stream is cut
-// into chunks run by separate workgroups).  Each key tile is staged in LDS once (K as
-// [key][dim], V transposed to [dim][key]) and used by all four wavefronts; scores are masked per
-// element by "key slot inside this query's segment range", and one online softmax runs across
+// into chunks run by separate workgroups).  Each key tile goes straight from global memory
+// into LDS once (K and V both as [key][dim]; V^T is produced by transposing LDS reads) and is
+// used by all four wavefronts; scores are masked per element by "key slot inside this query's
+// segment range", and one online softmax runs across
 // the question-key and segment-key tiles, which is the single softmax over the union that the
 // definition asks for.  Chunked owners leave (unnormalised O, max, sum) partials that the
 // finalize kernel merges with the usual log-sum-exp rule.
