@@ -218,7 +218,10 @@ def main():
                             "frac_hbm": 30.0 * tokens / t_build / 1e9 / PEAK_HBM_GBS},
     }
     if not args.no_cpu_baseline and w.do is not None:
-        sample = [(0, 0), (0, H - 1)]
+        # equal numbers of row and column heads, every sequence: about 10-30 s of CPU work
+        rows_h = [h for h in range(H) if hk[h] == 0][:2]
+        cols_h = [h for h in range(H) if hk[h] == 1][:2]
+        sample = [(b, h) for b in range(min(B, 2)) for h in rows_h + cols_h]
         res["cpu_baseline"] = cpu_baseline(w, sample, B * H)
     print(json.dumps(res))
 
