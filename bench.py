@@ -76,6 +76,55 @@ def cpu_baseline(w, pairs, total_heads):
                        "segment tables not included")
 
 
+def breakeven(steps, warmup):
+    """Section 3.1 uses the faster of two equivalent implementations per sequence length: times
+    both here on tables shaped like configuration 2 (B=32, H=12, 4 columns, short cells)."""
+    import torch
+    from paper_2109_04312_amd import mate, synth
+    torch.cuda.set_device(0)
+    B, H, rows = 32, 12, []
+    for N in (64, 128, 256, 384, 512, 768, 1024):
+        rng = np.random.default_rng(synth.BASE_SEED + N)
+        G, C = max(4, N // 16), 4
+        R = max(2, int((N - G) * 0.85 / (C * 2)))
+        st = synth._stack([synth.flatten_table(N, G, R, C, synth.geometric_lengths(rng, 2.0, 8, R * C))
+                           for _ in range(B)])
+        q, k, v, do = (torch.from_numpy(x).to(torch.bfloat16).cuda()
+                       for x in synth.draw_tensors(rng, B, H, N, D, "bf16", 4))
+        r, c, f = (torch.from_numpy(x).cuda() for x in (st.row_ids, st.col_ids, st.flags))
+        hk = synth.half_row_half_col(H)
+        seg = mate.Segments(torch.empty(mate.mate_segments_bytes(B, N), dtype=torch.uint8, device="cuda"), B, N)
+        out, lse = torch.empty_like(q), torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        ws_f = mate.workspace(B, H, N, D, mate.MATE_BF16, False, "cuda")
+        ws_b = mate.workspace(B, H, N, D, mate.MATE_BF16, True, "cuda")
+        ws_d = torch.empty(mate.mate_dense_workspace_bytes(B, H, N), dtype=torch.uint8, device="cuda")
+
+        def seg_step():
+            mate.build_segments(r, c, f, out=seg)
+            mate.attn_fwd(q, k, v, seg, hk, 0.125, out=out, lse=lse, ws=ws_f)
+            mate.attn_bwd(q, k, v, out, lse, do, seg, hk, 0.125, dq=dq, dk=dk, dv=dv, ws=ws_b)
+
+        def dense_step():
+            mate.attn_fwd_dense(q, k, v, r, c, f, hk, 0.125, out=out, lse=lse)
+            mate.attn_bwd_dense(q, k, v, out, lse, do, r, c, f, hk, 0.125, dq=dq, dk=dk, dv=dv, ws=ws_d)
+
+        t = {}
+        for name, fn in (("segment", seg_step), ("dense", dense_step)):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            t[name] = (time.perf_counter() - t0) / steps * 1e6
+        rows.append({"N": N, "segment_us": round(t["segment"], 1), "dense_us": round(t["dense"], 1),
+                     "faster": min(t, key=t.get)})
+    print(json.dumps({"breakeven": rows, "B": B, "H": H, "dtype": "bf16", "steps": steps,
+                      "step": "segment: build + fwd + bwd; dense: fwd + bwd"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +135,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy three times (to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
+    ap.add_argument("--breakeven", action="store_true",
+                    help="only time the segment path (build + fwd + bwd) against the dense-mask "
+                         "entry points (fwd + bwd) at short sequence lengths and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -103,6 +155,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_each_way": src.numel() * 4}))
+        return
+
+    if args.breakeven:
+        breakeven(args.steps, args.warmup)
         return
 
     w = synth.make_config(args.config)

@@ -55,7 +55,10 @@ enum { MATE_TOK_LOCAL = 0, MATE_TOK_GLOBAL = 1, MATE_TOK_PAD = 2 };
 /* head_kind[h] */
 enum { MATE_HEAD_ROW = 0, MATE_HEAD_COL = 1 };
 
-enum { MATE_MAX_N = 16384, MATE_MAX_HEADS = 256, MATE_HEAD_DIM = 64 };
+enum { MATE_MAX_N = 16384, MATE_MAX_HEADS = 256, MATE_HEAD_DIM = 64,
+       MATE_DENSE_MAX_N = 1024 /* longest sequence of the dense-mask variant */,
+       MATE_DENSE_PREFERRED_MAX_N = 256 /* measured on MI355X: up to here the dense-mask
+                                           variant is the faster of the two */ };
 
 /* Device bytes needed for the segment tables of B sequences of length N (0 if out of range). */
 size_t mate_segments_bytes(int B, int N);
@@ -146,15 +149,42 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
                           size_t workspace_bytes, void* stream);
 
 /*
+ * Dense-mask variant for short sequences.  Section 3.1 keeps two functionally equivalent
+ * implementations (the reordered one above and plain attention under the mask of Section 3) and
+ * uses whichever is faster for the sequence length at hand.  These two calls are the second
+ * one: same results as mate_attn_fwd / mate_attn_bwd, no segment tables -- every (query, key)
+ * pair is scored and kept or dropped by comparing the tokens' ids and flags.
+ *
+ *   row_ids, col_ids, flags   [B, N] as for mate_build_segments (ids of table tokens must be
+ *                             >= 0; nothing checks that here)
+ *   t           MATE_BF16 only;  N <= MATE_DENSE_MAX_N;  otherwise MATE_ERR_UNSUPPORTED
+ *   workspace   backward only: mate_dense_workspace_bytes(B, H, N) bytes
+ * Everything else as above.  Asynchronous on `stream`; deterministic.
+ */
+size_t mate_dense_workspace_bytes(int B, int H, int N);
+mate_status mate_attn_fwd_dense(const void* q, const void* k, const void* v,
+                                const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, const uint8_t* head_kind, int B, int H,
+                                int N, int D, mate_dtype t, float scale, void* out, float* lse,
+                                void* stream);
+mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, const void* out,
+                                const float* lse, const void* dout, const int32_t* row_ids,
+                                const int32_t* col_ids, const uint8_t* flags,
+                                const uint8_t* head_kind, int B, int H, int N, int D,
+                                mate_dtype t, float scale, void* dq, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hook, not part of the computation: arms the calling thread so that the next
- * launch of the named kernel (inside mate_build_segments / mate_attn_fwd / mate_attn_bwd) is
+ * launch of the named kernel (inside mate_build_segments / mate_attn_fwd* / mate_attn_bwd*) is
  * bracketed by hipEventRecord(start_event) and hipEventRecord(stop_event) on the stream of that
  * call; the hook disarms itself once used.  The events are hipEvent_t handles passed as void*,
  * created with timing enabled and owned by the caller.  kernel = MATE_KERNEL_NONE disarms.
  * This is the only state the library keeps (per host thread).
  */
 enum { MATE_KERNEL_NONE = 0, MATE_KERNEL_BUILD = 1, MATE_KERNEL_FWD = 2, MATE_KERNEL_BWD_DQ = 3,
-       MATE_KERNEL_BWD_DKV = 4 };
+       MATE_KERNEL_BWD_DKV = 4, MATE_KERNEL_FWD_DENSE = 5, MATE_KERNEL_BWD_DQ_DENSE = 6,
+       MATE_KERNEL_BWD_DKV_DENSE = 7 };
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event);
 
 /* Static, NUL-terminated description of a status code (HOST pointer, never NULL). */

@@ -162,8 +162,66 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
 }
 
+namespace {
+mate_status fill_dense(DenseArgs& a, const int32_t* row_ids, const int32_t* col_ids,
+                       const uint8_t* flags, const uint8_t* head_kind, int B, int H, int N, int D,
+                       mate_dtype t, float scale) {
+  if (!row_ids || !col_ids || !flags || !head_kind) return MATE_ERR_NULL;
+  if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS) return MATE_ERR_SHAPE;
+  if (D != MATE_HEAD_DIM || t != MATE_BF16 || N > MATE_DENSE_MAX_N) return MATE_ERR_UNSUPPORTED;
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) return MATE_ERR_UNSUPPORTED;
+  static_assert(MATE_DENSE_MAX_N == kDenseMaxN, "header and kernels disagree");
+  std::memset(&a, 0, sizeof(a));
+  for (int h = 0; h < H; ++h) {
+    if (head_kind[h] > MATE_HEAD_COL) return MATE_ERR_UNSUPPORTED;
+    a.head_kind[h] = head_kind[h];
+  }
+  a.row_ids = row_ids; a.col_ids = col_ids; a.flags = flags;
+  a.B = B; a.H = H; a.N = N; a.scale = scale;
+  return MATE_OK;
+}
+}  // namespace
+
+size_t mate_dense_workspace_bytes(int B, int H, int N) {
+  if (!shape_ok(B, N) || N > MATE_DENSE_MAX_N || H < 1 || H > MATE_MAX_HEADS) return 0;
+  return 2 * delta_bytes(B, H, N);
+}
+
+mate_status mate_attn_fwd_dense(const void* q, const void* k, const void* v,
+                                const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, const uint8_t* head_kind, int B, int H,
+                                int N, int D, mate_dtype t, float scale, void* out, float* lse,
+                                void* stream) {
+  if (!q || !k || !v || !out || !lse) return MATE_ERR_NULL;
+  DenseArgs a;
+  mate_status st = fill_dense(a, row_ids, col_ids, flags, head_kind, B, H, N, D, t, scale);
+  if (st != MATE_OK) return st;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse;
+  return launch_fwd_dense(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, const void* out,
+                                const float* lse, const void* dout, const int32_t* row_ids,
+                                const int32_t* col_ids, const uint8_t* flags,
+                                const uint8_t* head_kind, int B, int H, int N, int D,
+                                mate_dtype t, float scale, void* dq, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return MATE_ERR_NULL;
+  DenseArgs a;
+  mate_status st = fill_dense(a, row_ids, col_ids, flags, head_kind, B, H, N, D, t, scale);
+  if (st != MATE_OK) return st;
+  const size_t need = mate_dense_workspace_bytes(B, H, N);
+  if (!workspace || workspace_bytes < need) return MATE_ERR_WORKSPACE;
+  a.q = q; a.k = k; a.v = v; a.o = out; a.dout = dout;
+  a.lse = const_cast<float*>(lse);
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.delta = static_cast<float*>(workspace);
+  a.nlse = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(B, H, N));
+  return launch_bwd_dense(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event) {
-  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_BWD_DKV) return MATE_ERR_UNSUPPORTED;
+  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_BWD_DKV_DENSE) return MATE_ERR_UNSUPPORTED;
   if (kernel != MATE_KERNEL_NONE && (!start_event || !stop_event)) return MATE_ERR_NULL;
   g_profile_hook.kernel = kernel;
   g_profile_hook.start = static_cast<hipEvent_t>(start_event);

@@ -25,6 +25,21 @@ struct AttnArgs {
   float scale;
 };
 
+// Arguments of the dense-mask variant (no segment tables: ids and flags directly).
+constexpr int kDenseMaxN = 1024;
+struct DenseArgs {
+  const void *q, *k, *v, *o, *dout;
+  void* out;
+  float* lse;
+  void *dq, *dk, *dv;
+  float *delta, *nlse;      // backward scratch [B,H,N]: -rowsum(dO * O), -lse / scale
+  const int *row_ids, *col_ids;
+  const unsigned char* flags;
+  unsigned char head_kind[256];
+  int B, H, N;
+  float scale;
+};
+
 // Measurement hook: when `kernel` matches the kernel about to be launched, record `start`
 // before and `stop` after that one launch on its stream, then disarm.
 struct ProfileHook {
@@ -58,5 +73,7 @@ hipError_t launch_bwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);
 // bf16 MFMA kernels.
 hipError_t launch_fwd_mfma(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_bwd_mfma(const AttnArgs& a, hipStream_t stream);
+hipError_t launch_fwd_dense(const DenseArgs& a, hipStream_t stream);
+hipError_t launch_bwd_dense(const DenseArgs& a, hipStream_t stream);
 
 }  // namespace mate

@@ -26,10 +26,14 @@ MATE_HEAD_ROW, MATE_HEAD_COL = 0, 1
 MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
-           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_profile_kernel",
+           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
+           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_profile_kernel",
            "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
 MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
+MATE_KERNEL_FWD_DENSE, MATE_KERNEL_BWD_DQ_DENSE, MATE_KERNEL_BWD_DKV_DENSE = 5, 6, 7
+MATE_DENSE_MAX_N = 1024
+MATE_DENSE_PREFERRED_MAX_N = 256
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2109_04312_amd.build` "
@@ -50,6 +54,13 @@ _lib.mate_attn_fwd.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _
 _lib.mate_attn_bwd.restype = _i
 _lib.mate_attn_bwd.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
                                _p, _p, _p, _p, _sz, _p]
+_lib.mate_dense_workspace_bytes.restype = _sz
+_lib.mate_dense_workspace_bytes.argtypes = [_i, _i, _i]
+_lib.mate_attn_fwd_dense.restype = _i
+_lib.mate_attn_fwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _p, _p]
+_lib.mate_attn_bwd_dense.restype = _i
+_lib.mate_attn_bwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
+                                     _p, _p, _p, _p, _sz, _p]
 _lib.mate_profile_kernel.restype = _i
 _lib.mate_profile_kernel.argtypes = [_i, _p, _p]
 _lib.mate_status_string.restype = C.c_char_p
@@ -62,6 +73,9 @@ mate_segments_export = _lib.mate_segments_export
 mate_attn_fwd = _lib.mate_attn_fwd
 mate_attn_bwd = _lib.mate_attn_bwd
 mate_profile_kernel = _lib.mate_profile_kernel
+mate_dense_workspace_bytes = _lib.mate_dense_workspace_bytes
+mate_attn_fwd_dense = _lib.mate_attn_fwd_dense
+mate_attn_bwd_dense = _lib.mate_attn_bwd_dense
 
 
 def mate_status_string(status: int) -> str:
@@ -180,3 +194,44 @@ def attn_bwd(q, k, v, out, lse, dout, seg: Segments, head_kind, scale: float,
                          _dev(dk, "dk"), _dev(dv, "dv"), ws.data_ptr(), ws.numel(), _stream()),
            "mate_attn_bwd")
     return dq, dk, dv
+
+
+def attn_fwd_dense(q, k, v, row_ids, col_ids, flags, head_kind, scale: float, out=None, lse=None):
+    """Dense-mask variant (no segment tables); bf16, N <= MATE_DENSE_MAX_N."""
+    B, H, N, D = q.shape
+    hk = _head_kind_host(head_kind, H)
+    code = _dtype_code(q)
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    _check(mate_attn_fwd_dense(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(row_ids, "row_ids"),
+                               _dev(col_ids, "col_ids"), _dev(flags, "flags"), hk.ctypes.data,
+                               B, H, N, D, code, float(scale), _dev(out, "out"), _dev(lse, "lse"),
+                               _stream()), "mate_attn_fwd_dense")
+    return out, lse
+
+
+def attn_bwd_dense(q, k, v, out, lse, dout, row_ids, col_ids, flags, head_kind, scale: float,
+                   dq=None, dk=None, dv=None, ws=None):
+    B, H, N, D = q.shape
+    hk = _head_kind_host(head_kind, H)
+    code = _dtype_code(q)
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    if ws is None:
+        ws = torch.empty(max(mate_dense_workspace_bytes(B, H, N), 16), dtype=torch.uint8, device=q.device)
+    _check(mate_attn_bwd_dense(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"),
+                               _dev(lse, "lse"), _dev(dout, "dout"), _dev(row_ids, "row_ids"),
+                               _dev(col_ids, "col_ids"), _dev(flags, "flags"), hk.ctypes.data,
+                               B, H, N, D, code, float(scale), _dev(dq, "dq"), _dev(dk, "dk"),
+                               _dev(dv, "dv"), ws.data_ptr(), ws.numel(), _stream()),
+           "mate_attn_bwd_dense")
+    return dq, dk, dv
+
+
+def prefer_dense(N: int, dtype: torch.dtype = torch.bfloat16) -> bool:
+    """Which of the two equivalent implementations to call for sequence length N (the measured
+    break-even on MI355X; `python bench.py --breakeven` re-measures it)."""
+    return dtype == torch.bfloat16 and N <= MATE_DENSE_PREFERRED_MAX_N

@@ -29,21 +29,28 @@ def dev_structure(st: synth.Structure):
             torch.from_numpy(st.flags).cuda())
 
 
-def run_hip(w: synth.Workload, backward: bool):
-    """Whole path on the GPU through the C ABI; returns float64 numpy arrays."""
+def run_hip(w: synth.Workload, backward: bool, dense: bool = False):
+    """Whole path on the GPU through the C ABI; returns float64 numpy arrays.
+    dense=True: the dense-mask entry points (no segment tables; seg is returned as None)."""
     from paper_2109_04312_amd import mate
     r, c, f = dev_structure(w.structure)
-    seg = mate.build_segments(r, c, f)
+    seg = None if dense else mate.build_segments(r, c, f)
     q, k, v = (to_dev(x, w.dtype) for x in (w.q, w.k, w.v))
     # outputs start as NaN: a row that no workgroup writes cannot pass for a result
     nan_like = lambda t: torch.full_like(t, float("nan"))
-    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale, out=nan_like(q),
-                             lse=torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=q.device))
+    lse0 = torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=q.device)
+    if dense:
+        out, lse = mate.attn_fwd_dense(q, k, v, r, c, f, w.head_kind, w.scale, out=nan_like(q), lse=lse0)
+    else:
+        out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale, out=nan_like(q), lse=lse0)
     res = dict(o=out, lse=lse)
     if backward:
         do = to_dev(w.do, w.dtype)
-        dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale,
-                                   dq=nan_like(q), dk=nan_like(q), dv=nan_like(q))
+        outs = dict(dq=nan_like(q), dk=nan_like(q), dv=nan_like(q))
+        if dense:
+            dq, dk, dv = mate.attn_bwd_dense(q, k, v, out, lse, do, r, c, f, w.head_kind, w.scale, **outs)
+        else:
+            dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale, **outs)
         res.update(dq=dq, dk=dk, dv=dv)
     torch.cuda.synchronize()
     pad = torch.from_numpy(w.structure.flags == synth.TOK_PAD).to(q.device)[:, None, :].expand(q.shape[:3])
