@@ -16,7 +16,7 @@
 // atomics, no dependent loads.  Workgroup i serves queue i mod 8 (consecutive workgroups go to
 // consecutive XCDs, so a queue stays on one XCD and the units of one (sequence, head) pair
 // share an L2).  Column-head pairs are numbered c = b n_col + i and belong to queue c mod 8, row-
-// head pairs r = b n_row + i to queue r mod 8.  Order inside a queue, longest units first:
+// head pairs r = b n_row + i to queue (r + B n_col) mod 8.  Order inside a queue, longest units first:
 //   1. column heads: table-token (then pad) tile 0 of every pair, tile 1 of every pair, ...
 //   2. the first quarter of the question-token unit records of all pairs, the same way (all
 //      of the real ones unless most of the sequence is question tokens)
@@ -63,7 +63,10 @@ inline int unit_grid(int B, int H, int N, int n_col) {
 __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   const int T = a.seg.tiles, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
   const int q = blockIdx.x & 7;
-  const int nc = (a.B * n_col - q + 7) >> 3, nr = (a.B * n_row - q + 7) >> 3;  // pairs of this queue
+  // row-head pairs are dealt to the queues starting where the column-head pairs stopped, so that
+  // a handful of pairs still spreads over as many XCDs as possible
+  const int qr = (q - a.B * n_col) & 7;
+  const int nc = (a.B * n_col - q + 7) >> 3, nr = (a.B * n_row - qr + 7) >> 3;  // pairs of this queue
   const int T1 = (T + 3) >> 2;  // question-token units per pair in the early part of their list
   int t = blockIdx.x >> 3;
   // region -> (first pair, pairs, first record, records per pair)
@@ -103,7 +106,7 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
     h = a.head_order[c % n_col];
     w.view = 1;
   } else {
-    const int r = q + 8 * (j - nc);
+    const int r = qr + 8 * (j - nc);
     b = r / n_row;
     h = a.head_order[n_col + r % n_row];
     w.view = 0;
