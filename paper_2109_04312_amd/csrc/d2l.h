@@ -82,18 +82,20 @@ __device__ inline void issue_row_words(const void* base, int index, const void* 
 }
 
 // ---- waiting ------------------------------------------------------------------------------
-// "At most n of my vector-memory loads still outstanding" (n wave-uniform).  Loads complete in
-// issue order, so this retires everything issued before the last n.  n is rounded down to a
-// value with an encoding below (waiting for more is always safe).
+// "At most n of my vector-memory loads still outstanding" (n wave-uniform, 0 <= n; values above
+// kMax are treated as kMax).  Loads complete in issue order, so this retires everything issued
+// before the last n.  n is rounded down to a value with an encoding below (waiting for more is
+// always safe).
+template <int kMax = 12>
 __device__ inline void wait_vmcnt_le(int n) {
-  if (n >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-  else if (n >= 11) asm volatile("s_waitcnt vmcnt(11)" ::: "memory");
-  else if (n >= 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-  else if (n >= 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-  else if (n >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else if (n >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-  else if (n >= 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-  else if (n >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if (kMax >= 12 && n >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else if (kMax >= 11 && n >= 11) asm volatile("s_waitcnt vmcnt(11)" ::: "memory");
+  else if (kMax >= 10 && n >= 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+  else if (kMax >= 9 && n >= 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+  else if (kMax >= 8 && n >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if (kMax >= 6 && n >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  else if (kMax >= 5 && n >= 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+  else if (kMax >= 4 && n >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 

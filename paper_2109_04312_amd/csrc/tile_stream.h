@@ -87,7 +87,10 @@ struct TileStream {
   // Top of iteration t: tile t is complete in LDS for every wavefront, tile t - 1's stage is
   // free; keep the pipeline full.  Returns the stage holding tile t.
   __device__ const char* acquire(int t) {
-    wait_vmcnt_le(since[0]);  // my share of tile t has landed
+    // my share of tile t has landed (with two stages nothing is ever issued between a tile's
+    // data and the wait for it, so the count is known at compile time)
+    // (otherwise at most NS - 2 tiles' worth: 5 loads per tile and one index load each)
+    if (NS == 2) wait_vmcnt_le<0>(0); else wait_vmcnt_le<6 * (NS - 2)>(since[0]);
     barrier_no_fence();       // ... everyone's has, and everyone is done with tile t - 1
     if (t + 2 * NS - 2 < u.t_end) issue_idx(t + 2 * NS - 2);
     if (t + NS - 1 < u.t_end) issue_data(t + NS - 1, NS - 1);
