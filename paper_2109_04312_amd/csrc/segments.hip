@@ -56,16 +56,32 @@ __device__ inline int block_exclusive_scan(int v, int* tmp, int& total) {
   return base + inc - v;
 }
 
-// Lanes of the wavefront that hold the same digit as this lane (valid lanes only).
-__device__ inline unsigned long long match_digit(unsigned digit, bool valid) {
+// Number of set bits of `mask` that belong to lanes before this one (v_mbcnt).
+__device__ inline int lanes_before(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+}
+
+// Lanes of the wavefront that hold the same digit as this lane (valid lanes only).  Only the
+// bits of `vary` (wave-uniform: the bits in which the digits of this batch differ at all) need a
+// ballot each.
+__device__ inline unsigned long long match_digit(unsigned digit, bool valid, unsigned vary) {
   unsigned long long same = __ballot(valid);
-#pragma unroll
-  for (int bit = 0; bit < kDigitBits; ++bit) {
-    const bool one = (digit >> bit) & 1u;
+  for (unsigned v = vary; v; v &= v - 1u) {
+    const bool one = (digit >> (__ffs(v) - 1)) & 1u;
     const unsigned long long m = __ballot(one);
     same &= one ? m : ~m;
   }
   return same;
+}
+// Bits in which the digits of the valid lanes differ (wave-uniform).
+__device__ inline unsigned varying_bits(unsigned digit, bool valid) {
+  const unsigned long long vm = __ballot(valid);
+  if (vm == 0) return 0u;
+  const unsigned first = __builtin_amdgcn_readlane(digit, __ffsll((long long)vm) - 1);
+  unsigned d = valid ? digit ^ first : 0u;
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) d |= __shfl_xor(d, s, 64);
+  return __builtin_amdgcn_readfirstlane(d);
 }
 
 template <int P2>
@@ -108,7 +124,6 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   // batches of 64, lane = consecutive element, so that LDS and global accesses are unit-stride
   // and ranks inside a batch come from ballots.
   const int w0 = wave * CHUNK;
-  const unsigned long long below = (1ull << lane) - 1ull;  // lanes before this one
 
   // ---- classify; count the three kinds of position per wavefront ---------------------------
   unsigned char my_flag[NB];
@@ -159,10 +174,10 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int i = w0 + e * 64 + lane;
     const unsigned long long ml = __ballot(my_flag[e] == 0), mg = __ballot(my_flag[e] == 1),
                              mp = __ballot(my_flag[e] == 2);
-    if (my_flag[e] == 0) buf_a[l_at + __popcll(ml & below)] = (unsigned short)i;
+    if (my_flag[e] == 0) buf_a[l_at + lanes_before(ml)] = (unsigned short)i;
     if (view == 0) {
-      if (my_flag[e] == 1) global_idx[g_at + __popcll(mg & below)] = i;
-      if (my_flag[e] == 2) pad_idx[p_at + __popcll(mp & below)] = i;
+      if (my_flag[e] == 1) global_idx[g_at + lanes_before(mg)] = i;
+      if (my_flag[e] == 2) pad_idx[p_at + lanes_before(mp)] = i;
     }
     l_at += __popcll(ml);
     g_at += __popcll(mg);
@@ -196,8 +211,8 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
 #pragma unroll
     for (int e = 0; e < NB; ++e) {
       const bool valid = w0 + e * 64 + lane < L;
-      const unsigned long long same = match_digit(dig[e], valid);
-      const int before = __popcll(same & below);
+      const unsigned long long same = match_digit(dig[e], valid, varying_bits(dig[e], valid));
+      const int before = lanes_before(same);
       int old = 0;
       if (valid && before == 0) {  // first lane of a group of equal digits
         old = hist[wave][dig[e]];
@@ -262,7 +277,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int s = w0 + e * 64 + lane;
     const bool head = (head_bits >> e) & 1u;
     const unsigned long long mh = __ballot(head);
-    const int seg_idx = seg_at + __popcll(mh & below) + (head ? 1 : 0) - 1;  // heads up to and including me
+    const int seg_idx = seg_at + lanes_before(mh) + (head ? 1 : 0) - 1;  // heads up to and including me
     if (s < L) {
       perm[s] = my_pos[e];
       seg_of_tok[my_pos[e]] = seg_idx;
