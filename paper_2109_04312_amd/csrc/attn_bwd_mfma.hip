@@ -30,7 +30,7 @@ namespace {
 // dQ (and delta)
 // ======================================================================================
 constexpr int kDqStage = 2 * kTileBytes;          // K tile, V tile
-constexpr int kDqNS = 3, kDkvNS = 2;              // LDS stages of the two kernels
+constexpr int kDqNS = 2, kDkvNS = 2;              // LDS stages of the two kernels
 constexpr int kDkvStage = 2 * kTileBytes + 512;   // Q tile, dO tile, -lse/scale[64], -delta[64]
 
 __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
@@ -164,7 +164,9 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   store_owned_rows<1>(accs, muls, outs, lds, q_tok, wave, lane);
 }
 
-__global__ __launch_bounds__(kThreads) void bwd_dq_mfma_kernel(AttnArgs a) {
+// (four workgroups per CU: with three, the column-head units of the benchmark shape do not all
+// fit at once and the stragglers double the kernel's critical path)
+__global__ __launch_bounds__(kThreads, 4) void bwd_dq_mfma_kernel(AttnArgs a) {
   Work w;
   if (!take_unit(a, w)) return;
   bwd_dq_unit(a, w);
