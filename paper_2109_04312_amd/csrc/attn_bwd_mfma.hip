@@ -55,7 +55,8 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   const int* global_idx = a.seg.global_idx + (size_t)b * N;
 
   if (u.kind == UNIT_PAD) {
-    zero_pad_rows(dQ, u, tid);
+    unsigned short* const outs[1] = {dQ};
+    zero_pad_rows<1>(outs, u, tid);
     return;
   }
   // First round trip: which rows this workgroup owns, and the token indices of the first tiles.
@@ -197,8 +198,8 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   const int* global_idx = a.seg.global_idx + (size_t)b * N;
 
   if (u.kind == UNIT_PAD) {
-    zero_pad_rows(dK, u, tid);
-    zero_pad_rows(dV, u, tid);
+    unsigned short* const outs[2] = {dK, dV};
+    zero_pad_rows<2>(outs, u, tid);
     return;
   }
   // Q and dO tiles of the streamed queries go through the LDS ring, each read plain

@@ -49,9 +49,17 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   const int* global_idx = a.seg.global_idx + (size_t)b * N;
 
   if (u.kind == UNIT_PAD) {  // pad positions: O = 0, LSE = 0
-    zero_pad_rows(O, u, tid);
-    for (int x = tid; x < kPadSlots; x += kThreads)
-      if (u.t0 + x < u.own_count) LSE[u.own_list[u.t0 + x]] = 0.f;
+    unsigned short* const outs[1] = {O};
+    zero_pad_rows<1>(outs, u, tid);
+    int tok[kPadSlots / kThreads];
+#pragma unroll
+    for (int i = 0; i < kPadSlots / kThreads; ++i) {
+      const int row = u.t0 + tid + i * kThreads;
+      tok[i] = row < u.own_count ? u.own_list[row] : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kPadSlots / kThreads; ++i)
+      if (tok[i] >= 0) LSE[tok[i]] = 0.f;
     return;
   }
 

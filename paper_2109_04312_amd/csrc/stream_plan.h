@@ -225,13 +225,25 @@ __device__ inline void store_partial(const f32x16 acc[2], float mul, float* __re
                       acc[db][4 * g + 3] * mul);
 }
 
-__device__ inline void zero_pad_rows(unsigned short* __restrict__ out, const UnitPlan& u, int tid) {
-  for (int x = tid; x < kPadSlots * 8; x += kThreads) {
-    const int row = x >> 3, piece = x & 7;
-    if (u.t0 + row < u.own_count)
-      *reinterpret_cast<uint4*>(out + (size_t)u.own_list[u.t0 + row] * kD + piece * 8) =
-          make_uint4(0, 0, 0, 0);
+// Zero fill of the rows of a pad unit in kTensors tensors.  The positions of all the rows a
+// thread will write are loaded first (independent loads, one round trip), then the stores go
+// out back to back.
+template <int kTensors>
+__device__ inline void zero_pad_rows(unsigned short* const (&out)[kTensors], const UnitPlan& u, int tid) {
+  constexpr int kRounds = kPadSlots * 8 / kThreads;  // rows of 8 pieces; 32 rows per round
+  const int piece = tid & 7;
+  int tok[kRounds];
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) {
+    const int row = u.t0 + (tid >> 3) + i * (kThreads / 8);
+    tok[i] = row < u.own_count ? u.own_list[row] : -1;
   }
+#pragma unroll
+  for (int x = 0; x < kTensors; ++x)
+#pragma unroll
+    for (int i = 0; i < kRounds; ++i)
+      if (tok[i] >= 0)
+        *reinterpret_cast<uint4*>(out[x] + (size_t)tok[i] * kD + piece * 8) = make_uint4(0, 0, 0, 0);
 }
 
 __device__ inline bool tables_match(const AttnArgs& a) {
