@@ -16,6 +16,14 @@ What each function follows in the paper (arXiv 2109.04312):
   * build_segments      -- the per-head data-dependent, deterministic reordering of
                            Section 3.1 (row-order / column-order traversal), stated as a
                            stable sort plus run boundaries.
+  * bucketed_flags, bucketed_attention_mask
+                        -- the approximation of Section 3.1 ("Efficient implementation"):
+                           a global part of at most G tokens, the rest of each head's
+                           ordered input in buckets of R, a bucket attending to itself and
+                           to its two neighbours, further restricted by the row / column
+                           mask.  Every function below takes `bucketed=(G, R)` for it.
+                           PARITY UNPINNED for the readings listed under "bucketed" below:
+                           the paper leaves out the code that would decide them.
 
 Readings taken where the paper is silent (listed again in the design notes):
   * the softmax scale is an explicit argument (the equation has none, the appendix
@@ -25,6 +33,15 @@ Readings taken where the paper is silent (listed again in the design notes):
   * padding is a third flag value: pad keys get exactly zero weight, pad queries
     produce zero output and zero gradients;
   * local rows use ONE softmax over (global keys U own row/column keys).
+Bucketed mode (Section 3.1 and the description of the views in the appendix):
+  * the global part is the first G question tokens by position; question tokens beyond
+    it join the long part with the ids they carry (the section's claim that the two
+    implementations agree once G covers the question part holds exactly this way);
+  * the long part is the head's sorted order of table tokens (pads excluded), bucket j =
+    sorted slots [jR, (j+1)R); the last bucket may be short;
+  * "adjacent" does not wrap around: the first bucket has no left neighbour, the last no
+    right neighbour (a rotation would pair them; the row / column mask hides that pair
+    unless one segment spans the whole long part).
 
 Pins: tests/test_oracle_*.py (brute force from set notation, library SDPA special
 cases, closed forms, finite differences, permutation / relabelling invariants,
@@ -62,9 +79,56 @@ def attention_mask(row_ids, col_ids, flags, kind) -> np.ndarray:
     return m.astype(np.uint8)
 
 
-def useful_pairs(row_ids, col_ids, flags, kind) -> int:
+def useful_pairs(row_ids, col_ids, flags, kind, bucketed=None) -> int:
     """Number of (query, key) pairs with non-zero weight for one sequence and head kind."""
-    return int(attention_mask(row_ids, col_ids, flags, kind).sum(dtype=np.int64))
+    return int(_mask(row_ids, col_ids, flags, kind, bucketed).sum(dtype=np.int64))
+
+
+# --------------------------------------------------------------------------------------
+# Bucketed approximation (Section 3.1)
+# --------------------------------------------------------------------------------------
+def bucketed_flags(flags, global_length) -> np.ndarray:
+    """Flags of one sequence after the global part is cut at `global_length` tokens: the
+    question tokens past the first G (in position order) become table tokens."""
+    flags = np.array(flags, np.uint8, copy=True)
+    seen = 0
+    for p in range(flags.shape[0]):
+        if flags[p] == TOK_GLOBAL:
+            if seen >= global_length:
+                flags[p] = TOK_LOCAL
+            seen += 1
+    return flags
+
+
+def bucket_of_token(ids, flags, radius) -> np.ndarray:
+    """Bucket index of every table token of one sequence in one view (-1 for the others):
+    tokens ordered by id, ties by position; slot s of that order lies in bucket s // R."""
+    N = len(flags)
+    loc = [p for p in range(N) if flags[p] == TOK_LOCAL]
+    order = sorted(loc, key=lambda p: int(ids[p]))
+    bucket = np.full(N, -1, np.int64)
+    for slot, p in enumerate(order):
+        bucket[p] = slot // radius
+    return bucket
+
+
+def bucketed_attention_mask(row_ids, col_ids, flags, kind, global_length, radius) -> np.ndarray:
+    """mask[k, j] of Section 3.1 for one sequence: the pattern of Section 3 on the flags cut at
+    G, with a table-token pair kept only if the two buckets are equal or adjacent."""
+    fl = bucketed_flags(flags, global_length)
+    m = attention_mask(row_ids, col_ids, fl, kind).astype(bool)
+    ids = np.asarray(row_ids if kind == HEAD_ROW else col_ids)
+    bucket = bucket_of_token(ids, fl, radius)
+    is_l = fl == TOK_LOCAL
+    both_local = is_l[:, None] & is_l[None, :]
+    near = np.abs(bucket[:, None] - bucket[None, :]) <= 1
+    return (m & (~both_local | near)).astype(np.uint8)
+
+
+def _mask(row_ids, col_ids, flags, kind, bucketed):
+    if bucketed is None:
+        return attention_mask(row_ids, col_ids, flags, kind)
+    return bucketed_attention_mask(row_ids, col_ids, flags, kind, *bucketed)
 
 
 # --------------------------------------------------------------------------------------
@@ -85,10 +149,11 @@ def _head_forward(q, k, v, mask, scale):
     return o, lse, p
 
 
-def attn_forward(q, k, v, row_ids, col_ids, flags, head_kind, scale):
+def attn_forward(q, k, v, row_ids, col_ids, flags, head_kind, scale, bucketed=None):
     """q,k,v [B,H,N,D] -> (O [B,H,N,D] float64, LSE [B,H,N] float64).
 
     LSE_k = log sum_{j in A_k} exp(scale * q_k.k_j); rows of pad queries are 0 in both.
+    bucketed = (G, R) selects the pattern of Section 3.1 instead of Section 3's.
     """
     q = np.asarray(q, np.float64)
     k = np.asarray(k, np.float64)
@@ -101,7 +166,7 @@ def attn_forward(q, k, v, row_ids, col_ids, flags, head_kind, scale):
         for h in range(H):
             kind = int(head_kind[h])
             if kind not in masks:
-                masks[kind] = attention_mask(row_ids[b], col_ids[b], flags[b], kind)
+                masks[kind] = _mask(row_ids[b], col_ids[b], flags[b], kind, bucketed)
             o[b, h], lse[b, h], _ = _head_forward(q[b, h], k[b, h], v[b, h], masks[kind], scale)
     return o, lse
 
@@ -120,7 +185,7 @@ def _head_backward(q, k, v, do, mask, scale):
     return dq, dk, dv
 
 
-def attn_backward(q, k, v, do, row_ids, col_ids, flags, head_kind, scale):
+def attn_backward(q, k, v, do, row_ids, col_ids, flags, head_kind, scale, bucketed=None):
     """Gradients (dQ, dK, dV) [B,H,N,D] float64 of sum(O * dO); dO at pad queries is ignored."""
     q = np.asarray(q, np.float64)
     k = np.asarray(k, np.float64)
@@ -136,7 +201,7 @@ def attn_backward(q, k, v, do, row_ids, col_ids, flags, head_kind, scale):
         for h in range(H):
             kind = int(head_kind[h])
             if kind not in masks:
-                masks[kind] = attention_mask(row_ids[b], col_ids[b], flags[b], kind)
+                masks[kind] = _mask(row_ids[b], col_ids[b], flags[b], kind, bucketed)
             dq[b, h], dk[b, h], dv[b, h] = _head_backward(
                 q[b, h], k[b, h], v[b, h], do[b, h] * nonpad, masks[kind], scale)
     return dq, dk, dv
@@ -145,8 +210,10 @@ def attn_backward(q, k, v, do, row_ids, col_ids, flags, head_kind, scale):
 # --------------------------------------------------------------------------------------
 # Segment tables (Section 3.1: per-head reordering of the table tokens)
 # --------------------------------------------------------------------------------------
-def build_segments(row_ids, col_ids, flags):
+def build_segments(row_ids, col_ids, flags, bucketed=None):
     """Per-sequence integer tables, fixed-size arrays filled with -1 past their valid length.
+    bucketed = (G, R): the tables of the flags cut at G (Section 3.1), windows limited to the
+    neighbouring buckets.
 
     Returns a dict with
       counts      [B,4]  int32 : G (global), L (table), S_row, S_col
@@ -155,6 +222,9 @@ def build_segments(row_ids, col_ids, flags):
                                    (id, position) -- i.e. a stable sort by id
       seg_off     [2,B,N+1] int32: first sorted slot of each segment, then L
       seg_of_tok  [2,B,N]  int32 : segment index of each table token, -1 for others
+      window      [2,B,N,2] int32: per sorted slot, the range [lo, hi) of sorted slots whose
+                                   tokens it attends to: its segment, in bucketed mode cut
+                                   to buckets j-1 .. j+1 of its own bucket j; 0,0 past L
     """
     row_ids = np.asarray(row_ids)
     col_ids = np.asarray(col_ids)
@@ -165,6 +235,9 @@ def build_segments(row_ids, col_ids, flags):
     perm = np.full((2, B, N), -1, np.int32)
     seg_off = np.full((2, B, N + 1), -1, np.int32)
     seg_of_tok = np.full((2, B, N), -1, np.int32)
+    window = np.zeros((2, B, N, 2), np.int32)
+    if bucketed is not None:
+        flags = np.stack([bucketed_flags(flags[b], bucketed[0]) for b in range(B)])
     for b in range(B):
         glob = [p for p in range(N) if flags[b, p] == TOK_GLOBAL]
         loc = [p for p in range(N) if flags[b, p] == TOK_LOCAL]
@@ -182,5 +255,12 @@ def build_segments(row_ids, col_ids, flags):
                 seg_of_tok[view, b, p] = n_seg - 1
             seg_off[view, b, n_seg] = len(order)
             counts[b, 2 + view] = n_seg
+            for slot, p in enumerate(order):
+                g = seg_of_tok[view, b, p]
+                lo, hi = int(seg_off[view, b, g]), int(seg_off[view, b, g + 1])
+                if bucketed is not None:
+                    j, R = slot // bucketed[1], bucketed[1]
+                    lo, hi = max(lo, (j - 1) * R), min(hi, (j + 2) * R)
+                window[view, b, slot] = (lo, hi)
     return dict(counts=counts, global_idx=global_idx, perm=perm, seg_off=seg_off,
-                seg_of_tok=seg_of_tok)
+                seg_of_tok=seg_of_tok, window=window)
