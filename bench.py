@@ -37,22 +37,33 @@ TRAFFIC = {"cfg4_B2_N8192_H16": {
 }}
 
 
-def useful_pairs_per_view(st):
+def useful_pairs_per_view(st, bucketed=None):
     """[B,2] useful (query,key) pairs per sequence for a row head / a column head:
-    L*G + sum_i s_i^2 + G*T  (table->question, table->own segment, question->all)."""
+    L*G + sum_i s_i^2 + G*T  (table->question, table->own segment, question->all).
+    bucketed = (G, R): the question tokens past the first G count as table tokens and a table
+    token meets only the part of its segment in its own and the two adjacent buckets of R
+    sorted slots (Section 3.1)."""
     from paper_2109_04312_amd import synth
     out = np.zeros((st.B, 2), np.int64)
     for b in range(st.B):
-        f = st.flags[b]
+        f = st.flags[b].copy()
+        if bucketed is not None:
+            quest = np.flatnonzero(f == synth.TOK_GLOBAL)
+            f[quest[bucketed[0]:]] = synth.TOK_LOCAL
         G = int((f == synth.TOK_GLOBAL).sum())
         Lc = int((f == synth.TOK_LOCAL).sum())
         for v, ids in enumerate((st.row_ids[b], st.col_ids[b])):
-            _, s = np.unique(ids[f == synth.TOK_LOCAL], return_counts=True)
-            out[b, v] = Lc * G + int((s.astype(np.int64) ** 2).sum()) + G * (G + Lc)
+            srt = np.sort(ids[f == synth.TOK_LOCAL].astype(np.int64), kind="stable")
+            _, first, s = np.unique(srt, return_index=True, return_counts=True)
+            lo, hi = np.repeat(first, s), np.repeat(first + s, s)     # segment range per sorted slot
+            if bucketed is not None:
+                j = np.arange(Lc) // bucketed[1]
+                lo, hi = np.maximum(lo, (j - 1) * bucketed[1]), np.minimum(hi, (j + 2) * bucketed[1])
+            out[b, v] = Lc * G + int((hi - lo).sum()) + G * (G + Lc)
     return out
 
 
-def cpu_baseline(w, pairs, total_heads):
+def cpu_baseline(w, pairs, total_heads, bucketed=None):
     """Times the oracle (as it stands) on a few (b,h) pairs; scales to the whole batch."""
     from oracle import mate_oracle as orc
     try:
@@ -65,8 +76,8 @@ def cpu_baseline(w, pairs, total_heads):
     for b, h in pairs:
         sl = (slice(b, b + 1), slice(h, h + 1))
         args = (st.row_ids[b:b + 1], st.col_ids[b:b + 1], st.flags[b:b + 1], w.head_kind[h:h + 1], w.scale)
-        orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args)
-        orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args)
+        orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args, bucketed=bucketed)
+        orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args, bucketed=bucketed)
     dt = time.perf_counter() - t0
     B, H, N, _ = w.shape
     est = dt * total_heads / len(pairs)
@@ -131,6 +142,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration (default: headline 4)")
+    ap.add_argument("--bucketed", default=None, metavar="G,R",
+                    help="bucketed mode of Section 3.1 (the published models use 116,42)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy three times (to scale the "
@@ -178,8 +191,10 @@ def main():
     ws_b = mate.workspace(B, H, N, D, code, True, dev)
     hk = w.head_kind
 
+    bucketed = tuple(int(x) for x in args.bucketed.split(",")) if args.bucketed else None
+
     def step():
-        mate.build_segments(row, col, flg, out=seg)
+        mate.build_segments(row, col, flg, out=seg, bucketed=bucketed)
         mate.attn_fwd(q, k, v, seg, hk, w.scale, out=out, lse=lse, ws=ws_f)
         mate.attn_bwd(q, k, v, out, lse, do, seg, hk, w.scale, dq=dq, dk=dk, dv=dv, ws=ws_b)
 
@@ -224,7 +239,7 @@ def main():
     t_build, t_fwd = kernel_s["build_segments"], kernel_s["attn_fwd"]
     t_dq, t_dkv = kernel_s["attn_bwd_dq"], kernel_s["attn_bwd_dkv"]
 
-    pv = useful_pairs_per_view(st)
+    pv = useful_pairs_per_view(st, bucketed)
     pairs = int(sum(pv[b, int(hk[h])] for b in range(B) for h in range(H)))
     tokens = B * N
     nonpad = int((st.flags != synth.TOK_PAD).sum())
@@ -242,7 +257,7 @@ def main():
     alg_bytes = passes * 128 * nonpad * H
     hbm_gbs = alg_bytes / cand[dom][1] / 1e9
     t_attn = ms_per_step * 1e-3 - t_build
-    traffic = TRAFFIC.get(w.name, {}).get(dom)
+    traffic = None if bucketed else TRAFFIC.get(w.name, {}).get(dom)   # measured in the default mode
     traffic_detail = None
     if traffic is not None:
         traffic_detail = dict(traffic, unit="HBM bytes per launch",
@@ -254,9 +269,10 @@ def main():
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "B": B, "N": N, "H": H, "D": D, "row_heads": int((hk == 0).sum()),
+        "config": {"workload": w.name + (f"_bucketed_G{bucketed[0]}_R{bucketed[1]}" if bucketed else ""), "B": B, "N": N, "H": H, "D": D, "row_heads": int((hk == 0).sum()),
                    "col_heads": int((hk == 1).sum()), "non_pad_tokens": nonpad, "useful_pairs": pairs,
-                   "step": "mate_build_segments + mate_attn_fwd + mate_attn_bwd"},
+                   "step": ("mate_build_segments_bucketed" if bucketed else "mate_build_segments")
+                           + " + mate_attn_fwd + mate_attn_bwd"},
         "useful_tflops": 14 * D * pairs / (elapsed / args.steps) / 1e12,
         "useful_tflops_attn_only": 14 * D * pairs / t_attn / 1e12,
         "tokens_per_s_attn_only": tokens / t_attn,
@@ -278,7 +294,7 @@ def main():
         rows_h = [h for h in range(H) if hk[h] == 0][:2]
         cols_h = [h for h in range(H) if hk[h] == 1][:2]
         sample = [(b, h) for b in range(min(B, 2)) for h in rows_h + cols_h]
-        res["cpu_baseline"] = cpu_baseline(w, sample, B * H)
+        res["cpu_baseline"] = cpu_baseline(w, sample, B * H, bucketed)
     print(json.dumps(res))
 
 

@@ -82,7 +82,7 @@ size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bw
  *
  *   row_ids, col_ids  [B, N] int32, >= 0 for LOCAL tokens
  *   flags             [B, N] uint8, MATE_TOK_*
- *   segments          mate_segments_bytes(B, N) bytes, overwritten entirely
+ *   segments          mate_segments_bytes(B, N) bytes; every table in it is overwritten
  *
  * Asynchronous on `stream`.  A negative id on a LOCAL token or a flag > 2 does not stop the
  * build (the id is ordered as an unsigned number, the token is treated as padding) but sets
@@ -91,6 +91,31 @@ size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bw
 mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
                                 const uint8_t* flags, int B, int N, void* segments,
                                 void* stream);
+
+/*
+ * Segment builder of the bucketed mode -- the approximation of Section 3.1 ("Efficient
+ * implementation"): after each head kind has ordered its input, a global part of at most G
+ * tokens attends to and from everything, the rest is grouped in buckets of R consecutive
+ * tokens of that order, and a token attends to the global part and to the tokens of its own
+ * and the two adjacent buckets that share its row / column.  The appendix gives G = 116,
+ * R = 42 for the published models.  With G >= the number of question tokens and R >= the
+ * longest row / column the tables equal those of mate_build_segments (last sentence of the
+ * section's description).  The paper leaves out the code that fills the global part and builds
+ * the windows; this library reads it as:
+ *   - the global part is the first `global_length` GLOBAL tokens of a sequence by position;
+ *     the GLOBAL tokens after them are treated as LOCAL tokens with the ids they carry
+ *     (the paper gives question tokens row = column = 0), so their ids must be >= 0;
+ *   - bucket j is sorted slots [j R, (j + 1) R) of the head kind's order of LOCAL tokens;
+ *   - the first bucket has no left neighbour and the last no right neighbour (no wrap-around).
+ * mate_attn_fwd / mate_attn_bwd given these tables compute the bucketed attention; nothing
+ * else changes.  (The dense-mask variant has no bucketed form.)
+ *
+ *   global_length  G >= 0;  radius  R >= 1;  otherwise MATE_ERR_UNSUPPORTED
+ * Everything else as for mate_build_segments.
+ */
+mate_status mate_build_segments_bucketed(const int32_t* row_ids, const int32_t* col_ids,
+                                         const uint8_t* flags, int B, int N, int global_length,
+                                         int radius, void* segments, void* stream);
 
 /*
  * Copies the tables of one view to HOST arrays (test and inspection hook; waits for
@@ -108,6 +133,17 @@ mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
 mate_status mate_segments_export(const void* segments, int B, int N, int view, int32_t* perm,
                                  int32_t* seg_off, int32_t* seg_of_tok, int32_t* global_idx,
                                  int32_t* counts, void* stream);
+
+/*
+ * Copies the attention windows of one view to a HOST array (test and inspection hook; waits
+ * for `stream`): window[b][s] = {lo, hi}, the sorted slots [lo, hi) whose tokens slot s attends
+ * to besides the global part -- its segment, in bucketed mode cut to buckets j - 1 .. j + 1 of
+ * its own bucket j (Section 3.1).  Entries past L_b are {0, 0}.
+ *
+ *   window      HOST [B, N, 2] int32
+ */
+mate_status mate_segments_export_windows(const void* segments, int B, int N, int view,
+                                         int32_t* window, void* stream);
 
 /*
  * Forward pass: O[b,h,k,:] = sum_{j in A} softmax_j(scale * q_k . k_j) v_j with A the

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/mate.h"
@@ -75,10 +76,39 @@ mate_status mate_build_segments(const int32_t* row_ids, const int32_t* col_ids,
                                 void* stream) {
   if (!row_ids || !col_ids || !flags || !segments) return MATE_ERR_NULL;
   if (!shape_ok(B, N)) return MATE_ERR_SHAPE;
-  hipError_t e = launch_build_segments(row_ids, col_ids, flags, B, N,
+  hipError_t e = launch_build_segments(row_ids, col_ids, flags, B, N, N, 0,
                                        static_cast<int*>(segments),
                                        static_cast<hipStream_t>(stream));
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_build_segments_bucketed(const int32_t* row_ids, const int32_t* col_ids,
+                                         const uint8_t* flags, int B, int N, int global_length,
+                                         int radius, void* segments, void* stream) {
+  if (!row_ids || !col_ids || !flags || !segments) return MATE_ERR_NULL;
+  if (!shape_ok(B, N)) return MATE_ERR_SHAPE;
+  if (global_length < 0 || radius < 1) return MATE_ERR_UNSUPPORTED;
+  // a sequence has at most N question tokens and N slots: larger values change nothing
+  hipError_t e = launch_build_segments(row_ids, col_ids, flags, B, N, std::min(global_length, N),
+                                       std::min(radius, N), static_cast<int*>(segments),
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_segments_export_windows(const void* segments, int B, int N, int view,
+                                         int32_t* window, void* stream) {
+  if (!segments || !window) return MATE_ERR_NULL;
+  if (!shape_ok(B, N) || view < 0 || view > 1) return MATE_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const SegLayout lay(B, N);
+  const int* w = static_cast<const int*>(segments);
+  int head[kHdrWords];
+  if (hipMemcpyAsync(head, w, sizeof(head), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipMemcpyAsync(window, w + lay.view0 + (size_t)view * lay.view_stride + lay.slot_rng,
+                     (size_t)B * N * 2 * sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return MATE_ERR_HIP;
+  return head[0] == kMagic && head[1] == B && head[2] == N ? MATE_OK : MATE_ERR_SHAPE;
 }
 
 mate_status mate_segments_export(const void* segments, int B, int N, int view, int32_t* perm,

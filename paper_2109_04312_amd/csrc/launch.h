@@ -61,9 +61,11 @@ struct ProfileScope {
   }
 };
 
+// max_global >= N and radius = 0: the pattern of Section 3; otherwise the bucketed approximation
+// of Section 3.1 (global part of at most max_global tokens, windows of three buckets of radius).
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
-                                 const unsigned char* flags, int B, int N, int* seg,
-                                 hipStream_t stream);
+                                 const unsigned char* flags, int B, int N, int max_global,
+                                 int radius, int* seg, hipStream_t stream);
 
 // Scalar (non-MFMA) kernels: fp32 arithmetic throughout, one wavefront per query / key.
 // They serve dtype f32 and are the fallback-free reference-quality path for it.

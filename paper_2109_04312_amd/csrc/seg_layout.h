@@ -1,7 +1,8 @@
 // Layout of the caller-owned segment-table buffer (all int32 words), shared by the builder
 // kernel and the attention kernels.  Every array starts on a 16-byte boundary.
 //
-//   hdr[16]            magic, B, N, status (0 ok, 1 = bad id / flag seen), rest 0
+//   hdr[16]            magic, B, N, 0, global-part limit and radius of the bucketed mode (N and 0
+//                      without it), rest 0
 //   counts[B][12]      G, L, P (pad count), S_row, S_col, bad ids seen (rows, cols), rest 0
 //   global_idx[B][N]   ascending positions of GLOBAL tokens, -1 past G
 //   pad_idx[B][N]      ascending positions of PAD tokens, -1 past P
@@ -10,7 +11,8 @@
 //     perm[B][N]         sorted slot -> token position, -1 past L
 //     seg_off[B][N+1]    first slot of each segment, L at index S, -1 past that
 //     seg_of_tok[B][N]   token position -> segment index, -1 for GLOBAL / PAD
-//     slot_rng[B][N][2]  per sorted slot: [first slot, one-past-last slot) of its segment
+//     slot_rng[B][N][2]  per sorted slot: [first slot, one-past-last slot) of its window = its
+//                        segment, in bucketed mode cut to its own and the two adjacent buckets
 //     unit[B][T + 2][8]  work units of table-token owners (one per 128-slot tile of the sorted
 //                        order), then of pad owners (1024 pad positions each), then empty
 //                        records
@@ -20,7 +22,7 @@
 //   kind (0 none, 1 question-token owner, 2 table-token owner, 3 pad owner), first owned slot,
 //   streamed sorted-slot window [lo, hi), first and one-past-last streamed tile, partial-result
 //   slot or -1, 0
-// For a table-token owner [lo, hi) is the window spanned by the segments its 128 slots touch.
+// For a table-token owner [lo, hi) is the union of the windows of its 128 slots.
 // The streamed side of question-token owners is the whole sequence; it is cut into chunks of at
 // least kMinChunkTiles tiles, one unit each, that leave partial results.
 #pragma once

@@ -13,6 +13,12 @@
 // 128-slot tile of the sorted order the window of sorted slots its segments span, then the pad
 // tiles, and per sequence the chunks of the question-token owners.  The attention kernels map
 // a workgroup index to one of these records with arithmetic alone.
+//
+// Bucketed mode (the approximation of Section 3.1: a global part of at most G tokens, the rest
+// of the head's order in buckets of R, a bucket meeting itself and its two neighbours): the
+// question tokens past the first `max_global` are classified as table tokens, and every slot's
+// window is its segment cut to the slots of buckets j - 1 .. j + 1 of its own bucket j.  The
+// attention kernels read windows only, so the mode lives entirely in these tables.
 #include <hip/hip_runtime.h>
 
 #include "launch.h"
@@ -87,7 +93,8 @@ __device__ inline unsigned varying_bits(unsigned digit, bool valid) {
 template <int P2>
 __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int* __restrict__ row_ids, const int* __restrict__ col_ids,
-    const unsigned char* __restrict__ flags, int B, int N, int* __restrict__ seg) {
+    const unsigned char* __restrict__ flags, int B, int N, int max_global, int radius,
+    int* __restrict__ seg) {
   constexpr int CHUNK = P2 / kSegWaves;  // consecutive elements owned by one wavefront
   constexpr int NB = CHUNK / 64;         // 64-element batches per wavefront
   static_assert(NB >= 1, "P2 must be at least the workgroup size");
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   const unsigned char* fl = flags + (size_t)b * N;
 
   if (b == 0 && view == 0 && tid < kHdrWords)
-    seg[tid] = tid == 0 ? kMagic : tid == 1 ? B : tid == 2 ? N : 0;
+    seg[tid] = tid == 0 ? kMagic : tid == 1 ? B : tid == 2 ? N : tid == 4 ? max_global : tid == 5 ? radius : 0;
   if (tid == 0) { s_or = 0; s_bad = 0; }
   lds_barrier();
 
@@ -124,6 +131,32 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   // batches of 64, lane = consecutive element, so that LDS and global accesses are unit-stride
   // and ranks inside a batch come from ballots.
   const int w0 = wave * CHUNK;
+
+  // ---- bucketed mode: question tokens past the first max_global join the table tokens ----------
+  unsigned demote = 0;  // bit e: my element of batch e is such a token
+  if (max_global < N) {  // uniform; a sequence has at most N question tokens
+    int n_q = 0;
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const int i = w0 + e * 64 + lane;
+      n_q += __popcll(__ballot(i < N && fl[i] == 1));
+    }
+    if (lane == 0) wave_tot[1][wave] = n_q;
+    lds_barrier();
+    int q_at = 0;
+#pragma unroll
+    for (int w = 0; w < kSegWaves; ++w)
+      if (w < wave) q_at += wave_tot[1][w];
+    lds_barrier();  // wave_tot is written again below
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const int i = w0 + e * 64 + lane;
+      const bool is_q = i < N && fl[i] == 1;
+      const unsigned long long mq = __ballot(is_q);
+      if (is_q && q_at + lanes_before(mq) >= max_global) demote |= 1u << e;
+      q_at += __popcll(mq);
+    }
+  }
 
   // ---- classify; count the three kinds of position per wavefront ---------------------------
   unsigned char my_flag[NB];
@@ -135,6 +168,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     if (i < N) {
       f = fl[i];
       if (f > 2) { bad = 1; f = 2; }
+      if ((demote >> e) & 1u) f = 0;
       const int id = id_src[i];  // loaded for every position so that it does not wait for the flag
       if (f == 0) {
         if (id < 0) bad = 1;
@@ -291,15 +325,24 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   if (tid == 0) { seg_off[S] = L; counts[C_SROW + view] = S; }
   for (int i = S + 1 + tid; i <= N; i += kSegThreads) seg_off[i] = -1;
   lds_barrier();
-  auto seg_lo = [&](int s) { return (int)seg_start[seg_of_slot[s]]; };
-  auto seg_hi = [&](int s) {
+  // window of slot s: its segment, in bucketed mode cut to the neighbouring buckets.  Slots are
+  // below 2^14, so the bucket index comes exactly from one float multiply: (s + 0.5) / radius is
+  // at least 0.5 / radius away from an integer and the rounding error is below 2e-7 s / radius.
+  const float inv_radius = radius > 0 ? 1.0f / (float)radius : 0.f;
+  auto window = [&](int s) {
     const int g = seg_of_slot[s];
-    return g + 1 < S ? (int)seg_start[g + 1] : L;
+    int lo = seg_start[g], hi = g + 1 < S ? (int)seg_start[g + 1] : L;
+    if (radius > 0) {
+      const int first = (int)(((float)s + 0.5f) * inv_radius) * radius;  // first slot of s's bucket
+      lo = max(lo, first - radius);
+      hi = min(hi, first + 2 * radius);
+    }
+    return make_int2(lo, hi);
   };
 #pragma unroll
   for (int e = 0; e < NB; ++e) {
     const int s = w0 + e * 64 + lane;
-    if (s < N) slot_rng[s] = s < L ? make_int2(seg_lo(s), seg_hi(s)) : make_int2(0, 0);
+    if (s < N) slot_rng[s] = s < L ? window(s) : make_int2(0, 0);
   }
 
   // ---- work units of the attention kernels -------------------------------------------------
@@ -310,7 +353,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   if (tid < lay.tiles + 2) {
     int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
     if (tid < n_lt) {
-      const int t0 = tid * kTileSlots, lo = seg_lo(t0), hi = seg_hi(min(t0 + kTileSlots, L) - 1);
+      const int t0 = tid * kTileSlots, lo = window(t0).x, hi = window(min(t0 + kTileSlots, L) - 1).y;
       r0 = make_int4(UNIT_LOCAL, t0, lo, hi);
       r1.y = n_t0 + (hi - lo + BN - 1) / BN;
     } else if (tid < n_lt + n_pt) {
@@ -336,14 +379,14 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
 }
 
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
-                                 const unsigned char* flags, int B, int N, int* seg,
-                                 hipStream_t stream) {
+                                 const unsigned char* flags, int B, int N, int max_global,
+                                 int radius, int* seg, hipStream_t stream) {
   dim3 grid(B, 2), block(kSegThreads);
   ProfileScope prof(1, stream);
 #define MATE_SEG_CASE(P2)                                                                  \
   if (N <= P2) {                                                                            \
     hipLaunchKernelGGL(build_segments_kernel<P2>, grid, block, 0, stream, row_ids, col_ids, \
-                       flags, B, N, seg);                                                   \
+                       flags, B, N, max_global, radius, seg);                               \
     return hipGetLastError();                                                               \
   }
   MATE_SEG_CASE(1024)

@@ -26,7 +26,7 @@ MATE_HEAD_ROW, MATE_HEAD_COL = 0, 1
 MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
-           "mate_segments_export", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
+           "mate_build_segments_bucketed", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
            "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_profile_kernel",
            "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
@@ -47,6 +47,10 @@ _lib.mate_workspace_bytes.restype = _sz
 _lib.mate_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
 _lib.mate_build_segments.restype = _i
 _lib.mate_build_segments.argtypes = [_p, _p, _p, _i, _i, _p, _p]
+_lib.mate_build_segments_bucketed.restype = _i
+_lib.mate_build_segments_bucketed.argtypes = [_p, _p, _p, _i, _i, _i, _i, _p, _p]
+_lib.mate_segments_export_windows.restype = _i
+_lib.mate_segments_export_windows.argtypes = [_p, _i, _i, _i, _p, _p]
 _lib.mate_segments_export.restype = _i
 _lib.mate_segments_export.argtypes = [_p, _i, _i, _i, _p, _p, _p, _p, _p, _p]
 _lib.mate_attn_fwd.restype = _i
@@ -70,6 +74,8 @@ mate_segments_bytes = _lib.mate_segments_bytes
 mate_workspace_bytes = _lib.mate_workspace_bytes
 mate_build_segments = _lib.mate_build_segments
 mate_segments_export = _lib.mate_segments_export
+mate_build_segments_bucketed = _lib.mate_build_segments_bucketed
+mate_segments_export_windows = _lib.mate_segments_export_windows
 mate_attn_fwd = _lib.mate_attn_fwd
 mate_attn_bwd = _lib.mate_attn_bwd
 mate_profile_kernel = _lib.mate_profile_kernel
@@ -120,7 +126,8 @@ class Segments:
 
 
 def build_segments(row_ids: torch.Tensor, col_ids: torch.Tensor, flags: torch.Tensor,
-                   out: Segments | None = None) -> Segments:
+                   out: Segments | None = None, bucketed=None) -> Segments:
+    """bucketed = (global_length, radius) builds the tables of the bucketed mode."""
     B, N = flags.shape
     assert row_ids.dtype == torch.int32 and col_ids.dtype == torch.int32 and flags.dtype == torch.uint8
     assert row_ids.shape == (B, N) and col_ids.shape == (B, N)
@@ -129,9 +136,15 @@ def build_segments(row_ids: torch.Tensor, col_ids: torch.Tensor, flags: torch.Te
         raise MateError(MATE_ERR_SHAPE, "mate_segments_bytes")
     if out is None:
         out = Segments(torch.empty(nbytes, dtype=torch.uint8, device=flags.device), B, N)
-    _check(mate_build_segments(_dev(row_ids, "row_ids"), _dev(col_ids, "col_ids"),
-                               _dev(flags, "flags"), B, N, out.buf.data_ptr(), _stream()),
-           "mate_build_segments")
+    if bucketed is None:
+        _check(mate_build_segments(_dev(row_ids, "row_ids"), _dev(col_ids, "col_ids"),
+                                   _dev(flags, "flags"), B, N, out.buf.data_ptr(), _stream()),
+               "mate_build_segments")
+    else:
+        _check(mate_build_segments_bucketed(_dev(row_ids, "row_ids"), _dev(col_ids, "col_ids"),
+                                            _dev(flags, "flags"), B, N, int(bucketed[0]),
+                                            int(bucketed[1]), out.buf.data_ptr(), _stream()),
+               "mate_build_segments_bucketed")
     return out
 
 
@@ -146,8 +159,11 @@ def segments_export(seg: Segments, view: int) -> dict:
                                 seg_off.ctypes.data, seg_of_tok.ctypes.data,
                                 global_idx.ctypes.data, counts.ctypes.data, _stream()),
            "mate_segments_export")
+    window = np.empty((B, N, 2), np.int32)
+    _check(mate_segments_export_windows(seg.buf.data_ptr(), B, N, view, window.ctypes.data, _stream()),
+           "mate_segments_export_windows")
     return dict(perm=perm, seg_off=seg_off, seg_of_tok=seg_of_tok, global_idx=global_idx,
-                counts=counts)
+                counts=counts, window=window)
 
 
 def _head_kind_host(head_kind, H: int):

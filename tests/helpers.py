@@ -29,12 +29,13 @@ def dev_structure(st: synth.Structure):
             torch.from_numpy(st.flags).cuda())
 
 
-def run_hip(w: synth.Workload, backward: bool, dense: bool = False):
+def run_hip(w: synth.Workload, backward: bool, dense: bool = False, bucketed=None):
     """Whole path on the GPU through the C ABI; returns float64 numpy arrays.
-    dense=True: the dense-mask entry points (no segment tables; seg is returned as None)."""
+    dense=True: the dense-mask entry points (no segment tables; seg is returned as None).
+    bucketed=(G, R): the tables of the bucketed mode."""
     from paper_2109_04312_amd import mate
     r, c, f = dev_structure(w.structure)
-    seg = None if dense else mate.build_segments(r, c, f)
+    seg = None if dense else mate.build_segments(r, c, f, bucketed=bucketed)
     q, k, v = (to_dev(x, w.dtype) for x in (w.q, w.k, w.v))
     # outputs start as NaN: a row that no workgroup writes cannot pass for a result
     nan_like = lambda t: torch.full_like(t, float("nan"))
@@ -60,7 +61,7 @@ def run_hip(w: synth.Workload, backward: bool, dense: bool = False):
     return {n: t.float().cpu().numpy().astype(np.float64) for n, t in res.items()}, seg
 
 
-def run_oracle(w: synth.Workload, backward: bool, pairs=None):
+def run_oracle(w: synth.Workload, backward: bool, pairs=None, bucketed=None):
     """Oracle on all (b, h) or on the listed (b, h) pairs; returns {(b,h): dict of [N,..] arrays}."""
     st = w.structure
     B, H = w.q.shape[:2]
@@ -69,10 +70,10 @@ def run_oracle(w: synth.Workload, backward: bool, pairs=None):
     for b, h in pairs:
         sl = (slice(b, b + 1), slice(h, h + 1))
         args = (st.row_ids[b:b + 1], st.col_ids[b:b + 1], st.flags[b:b + 1], w.head_kind[h:h + 1], w.scale)
-        o, lse = orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args)
+        o, lse = orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args, bucketed=bucketed)
         d = dict(o=o[0, 0], lse=lse[0, 0])
         if backward:
-            dq, dk, dv = orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args)
+            dq, dk, dv = orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args, bucketed=bucketed)
             d.update(dq=dq[0, 0], dk=dk[0, 0], dv=dv[0, 0])
         res[(b, h)] = d
     return res
@@ -104,15 +105,16 @@ def compare(got: dict, ref: dict, w: synth.Workload, label=""):
     return worst
 
 
-def compare_segments(seg, st: synth.Structure):
+def compare_segments(seg, st: synth.Structure, bucketed=None):
     """Bit-exact comparison of every exported table with the oracle's."""
     from paper_2109_04312_amd import mate
-    ref = orc.build_segments(st.row_ids, st.col_ids, st.flags)
+    ref = orc.build_segments(st.row_ids, st.col_ids, st.flags, bucketed=bucketed)
     for view in (0, 1):
         got = mate.segments_export(seg, view)
         assert np.array_equal(got["perm"], ref["perm"][view]), f"perm view {view}"
         assert np.array_equal(got["seg_off"], ref["seg_off"][view]), f"seg_off view {view}"
         assert np.array_equal(got["seg_of_tok"], ref["seg_of_tok"][view]), f"seg_of_tok view {view}"
+        assert np.array_equal(got["window"], ref["window"][view]), f"window view {view}"
         assert np.array_equal(got["global_idx"], ref["global_idx"]), "global_idx"
         assert np.array_equal(got["counts"][:, 0], ref["counts"][:, 0])
         assert np.array_equal(got["counts"][:, 1], ref["counts"][:, 1])
