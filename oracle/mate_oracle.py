@@ -24,6 +24,8 @@ What each function follows in the paper (arXiv 2109.04312):
                            mask.  Every function below takes `bucketed=(G, R)` for it.
                            PARITY UNPINNED for the readings listed under "bucketed" below:
                            the paper leaves out the code that would decide them.
+  * cell_positions      -- Section 3.2: for long sequences the index of the positional
+                           embedding restarts at the beginning of each cell.
 
 Readings taken where the paper is silent (listed again in the design notes):
   * the softmax scale is an explicit argument (the equation has none, the appendix
@@ -33,6 +35,8 @@ Readings taken where the paper is silent (listed again in the design notes):
   * padding is a third flag value: pad keys get exactly zero weight, pad queries
     produce zero output and zero gradients;
   * local rows use ONE softmax over (global keys U own row/column keys).
+  * positional index: a cell is a maximal run of consecutive table tokens with the same
+    (row, column); question tokens keep their absolute position, pads get 0.
 Bucketed mode (Section 3.1 and the description of the views in the appendix):
   * the global part is the first G question tokens by position; question tokens beyond
     it join the long part with the ids they carry (the section's claim that the two
@@ -264,3 +268,29 @@ def build_segments(row_ids, col_ids, flags, bucketed=None):
                 window[view, b, slot] = (lo, hi)
     return dict(counts=counts, global_idx=global_idx, perm=perm, seg_off=seg_off,
                 seg_of_tok=seg_of_tok, window=window)
+
+
+# --------------------------------------------------------------------------------------
+# Positional index with a restart per cell (Section 3.2)
+# --------------------------------------------------------------------------------------
+def cell_positions(row_ids, col_ids, flags):
+    """[B,N] int32: index fed to the positional embedding.  A table token gets its offset from
+    the first token of its cell (a cell = consecutive table tokens sharing row and column), a
+    question token its position in the sequence, a pad 0."""
+    row_ids = np.asarray(row_ids)
+    col_ids = np.asarray(col_ids)
+    flags = np.asarray(flags)
+    B, N = flags.shape
+    out = np.zeros((B, N), np.int32)
+    for b in range(B):
+        start = 0
+        for p in range(N):
+            if flags[b, p] == TOK_GLOBAL:
+                out[b, p] = p
+            elif flags[b, p] == TOK_LOCAL:
+                same_cell = (p > 0 and flags[b, p - 1] == TOK_LOCAL
+                             and row_ids[b, p - 1] == row_ids[b, p] and col_ids[b, p - 1] == col_ids[b, p])
+                if not same_cell:
+                    start = p
+                out[b, p] = p - start
+    return out

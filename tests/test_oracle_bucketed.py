@@ -218,3 +218,4 @@ def test_backward_vs_finite_differences_in_bucketed_mode():
             xs[idx][pos] -= 2 * eps
             fd = (up - loss(*xs)) / (2 * eps)
             assert abs(fd - grad[pos]) < 1e-6, (name, pos)
+
