@@ -118,6 +118,24 @@ mate_status mate_build_segments_bucketed(const int32_t* row_ids, const int32_t* 
                                          int radius, void* segments, void* stream);
 
 /*
+ * Positional index with a restart per cell -- Section 3.2: for sequences longer than 512
+ * tokens the index of the positional embedding is reset at the beginning of each cell.
+ * Integer work only; independent of the segment tables.
+ *
+ * A cell is a maximal run of consecutive LOCAL positions with equal (row id, column id).
+ *   positions[b, k] = k - (first position of k's cell)   for LOCAL tokens
+ *                   = k                                   for GLOBAL tokens
+ *                   = 0                                   for PAD tokens (and flags > 2)
+ *
+ *   row_ids, col_ids, flags   [B, N] as for mate_build_segments
+ *   positions                 [B, N] int32, overwritten
+ * Asynchronous on `stream`.
+ */
+mate_status mate_cell_positions(const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, int B, int N, int32_t* positions,
+                                void* stream);
+
+/*
  * Copies the tables of one view to HOST arrays (test and inspection hook; waits for
  * `stream`).  Any output pointer may be NULL.  Entries past the valid length are -1.
  *

@@ -111,6 +111,16 @@ mate_status mate_segments_export_windows(const void* segments, int B, int N, int
   return head[0] == kMagic && head[1] == B && head[2] == N ? MATE_OK : MATE_ERR_SHAPE;
 }
 
+mate_status mate_cell_positions(const int32_t* row_ids, const int32_t* col_ids,
+                                const uint8_t* flags, int B, int N, int32_t* positions,
+                                void* stream) {
+  if (!row_ids || !col_ids || !flags || !positions) return MATE_ERR_NULL;
+  if (!shape_ok(B, N)) return MATE_ERR_SHAPE;
+  hipError_t e = launch_cell_positions(row_ids, col_ids, flags, B, N, positions,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
 mate_status mate_segments_export(const void* segments, int B, int N, int view, int32_t* perm,
                                  int32_t* seg_off, int32_t* seg_of_tok, int32_t* global_idx,
                                  int32_t* counts, void* stream) {

@@ -67,6 +67,10 @@ hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
                                  const unsigned char* flags, int B, int N, int max_global,
                                  int radius, int* seg, hipStream_t stream);
 
+// Positional index restarting at each cell (Section 3.2); out is [B, N] int32.
+hipError_t launch_cell_positions(const int* row_ids, const int* col_ids, const unsigned char* flags,
+                                 int B, int N, int* out, hipStream_t stream);
+
 // Scalar (non-MFMA) kernels: fp32 arithmetic throughout, one wavefront per query / key.
 // They serve dtype f32 and are the fallback-free reference-quality path for it.
 hipError_t launch_fwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);

@@ -26,7 +26,7 @@ MATE_HEAD_ROW, MATE_HEAD_COL = 0, 1
 MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
-           "mate_build_segments_bucketed", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
+           "mate_build_segments_bucketed", "mate_cell_positions", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
            "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_profile_kernel",
            "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
@@ -51,6 +51,8 @@ _lib.mate_build_segments_bucketed.restype = _i
 _lib.mate_build_segments_bucketed.argtypes = [_p, _p, _p, _i, _i, _i, _i, _p, _p]
 _lib.mate_segments_export_windows.restype = _i
 _lib.mate_segments_export_windows.argtypes = [_p, _i, _i, _i, _p, _p]
+_lib.mate_cell_positions.restype = _i
+_lib.mate_cell_positions.argtypes = [_p, _p, _p, _i, _i, _p, _p]
 _lib.mate_segments_export.restype = _i
 _lib.mate_segments_export.argtypes = [_p, _i, _i, _i, _p, _p, _p, _p, _p, _p]
 _lib.mate_attn_fwd.restype = _i
@@ -74,6 +76,7 @@ mate_segments_bytes = _lib.mate_segments_bytes
 mate_workspace_bytes = _lib.mate_workspace_bytes
 mate_build_segments = _lib.mate_build_segments
 mate_segments_export = _lib.mate_segments_export
+mate_cell_positions = _lib.mate_cell_positions
 mate_build_segments_bucketed = _lib.mate_build_segments_bucketed
 mate_segments_export_windows = _lib.mate_segments_export_windows
 mate_attn_fwd = _lib.mate_attn_fwd
@@ -145,6 +148,19 @@ def build_segments(row_ids: torch.Tensor, col_ids: torch.Tensor, flags: torch.Te
                                             _dev(flags, "flags"), B, N, int(bucketed[0]),
                                             int(bucketed[1]), out.buf.data_ptr(), _stream()),
                "mate_build_segments_bucketed")
+    return out
+
+
+def cell_positions(row_ids: torch.Tensor, col_ids: torch.Tensor, flags: torch.Tensor,
+                   out: torch.Tensor | None = None) -> torch.Tensor:
+    B, N = flags.shape
+    assert row_ids.dtype == torch.int32 and col_ids.dtype == torch.int32 and flags.dtype == torch.uint8
+    assert row_ids.shape == (B, N) and col_ids.shape == (B, N)
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.int32, device=flags.device)
+    assert out.dtype == torch.int32 and out.shape == (B, N)
+    _check(mate_cell_positions(_dev(row_ids, "row_ids"), _dev(col_ids, "col_ids"), _dev(flags, "flags"),
+                               B, N, _dev(out, "positions"), _stream()), "mate_cell_positions")
     return out
 
 

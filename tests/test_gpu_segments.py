@@ -80,3 +80,40 @@ def test_segments_rebuild_is_deterministic_and_reusable():
     mate.build_segments(r, c, f, out=seg)
     torch.cuda.synchronize()
     assert torch.equal(seg.buf, a)
+
+
+def _positions(st):
+    from oracle import mate_oracle as orc
+    from paper_2109_04312_amd import mate
+    r, c, f = hp.dev_structure(st)
+    out = torch.full(f.shape, -7, dtype=torch.int32, device="cuda")
+    mate.cell_positions(r, c, f, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), orc.cell_positions(st.row_ids, st.col_ids, st.flags))
+
+
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 1000, 1024, 1025, 4097, 8192, 9000, 16384])
+def test_cell_positions_sizes(N):
+    """Positional index restarting per cell, bit-exact: cells of 1..40 tokens crossing batch
+    and wavefront boundaries, in table order and with positions shuffled."""
+    print(f"cell positions N={N}", flush=True)
+    rng = np.random.default_rng(N)
+    for scatter in (False, True):
+        st = synth.random_structure(rng, 3, N, max_rows=max(1, min(300, N // 3)), max_cols=12,
+                                    max_global=min(N, 40), max_cell=40, scatter=scatter)
+        _positions(st)
+
+
+@pytest.mark.parametrize("idx", [1, 4, 5, 6])
+def test_cell_positions_benchmark_configs(idx):
+    _positions(synth.make_config(idx, tensors=False).structure)
+
+
+def test_cell_positions_one_long_cell_and_all_kinds():
+    N = 5000
+    L, G, P = synth.TOK_LOCAL, synth.TOK_GLOBAL, synth.TOK_PAD
+    flags = np.stack([np.full(N, L), np.full(N, G), np.full(N, P), np.full(N, L)]).astype(np.uint8)
+    row = np.zeros((4, N), np.int32)
+    col = np.zeros((4, N), np.int32)
+    row[3] = np.arange(N)                    # every token its own cell
+    _positions(synth.Structure(row, col, flags))   # sequence 0: one cell of 5000 tokens
