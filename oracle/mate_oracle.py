@@ -26,6 +26,12 @@ What each function follows in the paper (arXiv 2109.04312):
                            the paper leaves out the code that would decide them.
   * cell_positions      -- Section 3.2: for long sequences the index of the positional
                            embedding restarts at the beginning of each cell.
+  * project_qkv, project_out
+                        -- the projections either side of the attention: W_Q^i X_k, W_K^i X_j,
+                           W_V^i X_j of the head equation of Section 3 for all heads at once,
+                           and the usual output projection over the concatenated heads (the
+                           equation stops at the head; the model is a standard Transformer
+                           layer otherwise).
 
 Readings taken where the paper is silent (listed again in the design notes):
   * the softmax scale is an explicit argument (the equation has none, the appendix
@@ -294,3 +300,34 @@ def cell_positions(row_ids, col_ids, flags):
                     start = p
                 out[b, p] = p - start
     return out
+
+
+# --------------------------------------------------------------------------------------
+# Projections either side of the attention (head equation of Section 3)
+# --------------------------------------------------------------------------------------
+def project_qkv(x, w_qkv, bias, flags, n_heads):
+    """x [B,N,E];  w_qkv [3*H*m, E] holds the rows of W_Q^0 .. W_Q^{H-1}, then W_K^i, then W_V^i
+    (m rows per head);  bias [3*H*m] or None.  Returns q, k, v [B,H,N,m] float64 with
+    q[b,i,k,:] = W_Q^i x[b,k,:] (+ bias); rows of pad tokens are 0."""
+    x = np.asarray(x, np.float64)
+    w = np.asarray(w_qkv, np.float64)
+    B, N, E = x.shape
+    m = w.shape[0] // (3 * n_heads)
+    y = x @ w.T
+    if bias is not None:
+        y = y + np.asarray(bias, np.float64)
+    y = y * (np.asarray(flags) != TOK_PAD)[:, :, None]
+    y = y.reshape(B, N, 3, n_heads, m)
+    return tuple(np.ascontiguousarray(y[:, :, t].transpose(0, 2, 1, 3)) for t in range(3))
+
+
+def project_out(o, w_o, bias, flags):
+    """o [B,H,N,m];  w_o [E, H*m];  bias [E] or None.  y[b,k,:] = w_o . concat_i o[b,i,k,:]
+    (+ bias), float64 [B,N,E]; rows of pad tokens are 0."""
+    o = np.asarray(o, np.float64)
+    B, H, N, m = o.shape
+    cat = o.transpose(0, 2, 1, 3).reshape(B, N, H * m)
+    y = cat @ np.asarray(w_o, np.float64).T
+    if bias is not None:
+        y = y + np.asarray(bias, np.float64)
+    return y * (np.asarray(flags) != TOK_PAD)[:, :, None]
