@@ -229,8 +229,36 @@ mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, con
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The projections either side of the attention, bf16 on the matrix cores.
+ *
+ * mate_qkv_project: q[b,i,k,:] = W_Q^i x[b,k,:] (+ bias), likewise K and V -- the products
+ * W_Q^i X_k, W_K^i X_j, W_V^i X_j of the head equation of Section 3 for all heads at once,
+ * written directly in the [B, H, N, 64] layout mate_attn_fwd reads.
+ * mate_out_project: y[b,k,:] = W_O concat_i o[b,i,k,:] (+ bias), the output projection of a
+ * standard Transformer layer (the paper's equation stops at the head), reading the attention
+ * output in the layout mate_attn_fwd writes.
+ * Rows of PAD tokens are written as zeros (token tiles of padding only are not computed).
+ *
+ *   x       [B, N, E] bf16            w_qkv  [3*H*64, E] bf16: the 64 rows of W_Q^0 .. W_Q^{H-1},
+ *                                            then of W_K^i, then of W_V^i
+ *   o       [B, H, N, 64] bf16        w_o    [E, H*64] bf16
+ *   bias    [3*H*64] / [E] float, DEVICE, may be NULL
+ *   flags   [B, N] uint8, MATE_TOK_*
+ *   q,k,v   [B, H, N, 64] bf16        y      [B, N, E] bf16
+ *   t       MATE_BF16 only; H even; E a multiple of 128; otherwise MATE_ERR_UNSUPPORTED
+ * fp32 accumulation, one rounding to bf16 on store.  Asynchronous on `stream`; deterministic.
+ */
+mate_status mate_qkv_project(const void* x, const void* w_qkv, const float* bias,
+                             const uint8_t* flags, int B, int N, int H, int E, mate_dtype t,
+                             void* q, void* k, void* v, void* stream);
+mate_status mate_out_project(const void* o, const void* w_o, const float* bias,
+                             const uint8_t* flags, int B, int N, int H, int E, mate_dtype t,
+                             void* y, void* stream);
+
+/*
  * Measurement hook, not part of the computation: arms the calling thread so that the next
- * launch of the named kernel (inside mate_build_segments / mate_attn_fwd* / mate_attn_bwd*) is
+ * launch of the named kernel (inside mate_build_segments / mate_attn_fwd* / mate_attn_bwd* /
+ * mate_*_project) is
  * bracketed by hipEventRecord(start_event) and hipEventRecord(stop_event) on the stream of that
  * call; the hook disarms itself once used.  The events are hipEvent_t handles passed as void*,
  * created with timing enabled and owned by the caller.  kernel = MATE_KERNEL_NONE disarms.
@@ -238,7 +266,7 @@ mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, con
  */
 enum { MATE_KERNEL_NONE = 0, MATE_KERNEL_BUILD = 1, MATE_KERNEL_FWD = 2, MATE_KERNEL_BWD_DQ = 3,
        MATE_KERNEL_BWD_DKV = 4, MATE_KERNEL_FWD_DENSE = 5, MATE_KERNEL_BWD_DQ_DENSE = 6,
-       MATE_KERNEL_BWD_DKV_DENSE = 7 };
+       MATE_KERNEL_BWD_DKV_DENSE = 7, MATE_KERNEL_QKV_PROJECT = 8, MATE_KERNEL_OUT_PROJECT = 9 };
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event);
 
 /* Static, NUL-terminated description of a status code (HOST pointer, never NULL). */

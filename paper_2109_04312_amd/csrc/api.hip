@@ -156,6 +156,36 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
   return bad ? MATE_ERR_BAD_ID : MATE_OK;
 }
 
+namespace {
+mate_status proj_args_ok(int B, int N, int H, int E, mate_dtype t) {
+  if (!shape_ok(B, N) || H < 1 || H > MATE_MAX_HEADS || E < 1) return MATE_ERR_SHAPE;
+  if (t != MATE_BF16 || (H & 1) || E % 128 != 0 || E > 65536) return MATE_ERR_UNSUPPORTED;
+  return MATE_OK;
+}
+}  // namespace
+
+mate_status mate_qkv_project(const void* x, const void* w_qkv, const float* bias,
+                             const uint8_t* flags, int B, int N, int H, int E, mate_dtype t,
+                             void* q, void* k, void* v, void* stream) {
+  if (!x || !w_qkv || !flags || !q || !k || !v) return MATE_ERR_NULL;
+  const mate_status st = proj_args_ok(B, N, H, E, t);
+  if (st != MATE_OK) return st;
+  hipError_t e = launch_qkv_project(x, w_qkv, bias, flags, B, N, H, E, q, k, v,
+                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_out_project(const void* o, const void* w_o, const float* bias,
+                             const uint8_t* flags, int B, int N, int H, int E, mate_dtype t,
+                             void* y, void* stream) {
+  if (!o || !w_o || !flags || !y) return MATE_ERR_NULL;
+  const mate_status st = proj_args_ok(B, N, H, E, t);
+  if (st != MATE_OK) return st;
+  hipError_t e = launch_out_project(o, w_o, bias, flags, B, N, H, E, y,
+                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
 mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const void* segments,
                           const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
                           float scale, void* out, float* lse, void* workspace,

@@ -71,6 +71,16 @@ hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
 hipError_t launch_cell_positions(const int* row_ids, const int* col_ids, const unsigned char* flags,
                                  int B, int N, int* out, hipStream_t stream);
 
+// Projections either side of the attention (bf16): x [B,N,E] -> q, k, v [B,H,N,64] with
+// w_qkv [3*H*64, E]; o [B,H,N,64] -> y [B,N,E] with w_o [E, H*64].  bias may be null.
+// H even, E a multiple of 128.
+hipError_t launch_qkv_project(const void* x, const void* w_qkv, const float* bias,
+                              const unsigned char* flags, int B, int N, int H, int E, void* q,
+                              void* k, void* v, hipStream_t stream);
+hipError_t launch_out_project(const void* o, const void* w_o, const float* bias,
+                              const unsigned char* flags, int B, int N, int H, int E, void* y,
+                              hipStream_t stream);
+
 // Scalar (non-MFMA) kernels: fp32 arithmetic throughout, one wavefront per query / key.
 // They serve dtype f32 and are the fallback-free reference-quality path for it.
 hipError_t launch_fwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);

@@ -27,11 +27,12 @@ MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
            "mate_build_segments_bucketed", "mate_cell_positions", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
-           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_profile_kernel",
+           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
            "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
 MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
 MATE_KERNEL_FWD_DENSE, MATE_KERNEL_BWD_DQ_DENSE, MATE_KERNEL_BWD_DKV_DENSE = 5, 6, 7
+MATE_KERNEL_QKV_PROJECT, MATE_KERNEL_OUT_PROJECT = 8, 9
 MATE_DENSE_MAX_N = 1024
 MATE_DENSE_PREFERRED_MAX_N = 256
 
@@ -67,6 +68,10 @@ _lib.mate_attn_fwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i,
 _lib.mate_attn_bwd_dense.restype = _i
 _lib.mate_attn_bwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
                                      _p, _p, _p, _p, _sz, _p]
+_lib.mate_qkv_project.restype = _i
+_lib.mate_qkv_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p, _p, _p]
+_lib.mate_out_project.restype = _i
+_lib.mate_out_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p]
 _lib.mate_profile_kernel.restype = _i
 _lib.mate_profile_kernel.argtypes = [_i, _p, _p]
 _lib.mate_status_string.restype = C.c_char_p
@@ -85,6 +90,8 @@ mate_profile_kernel = _lib.mate_profile_kernel
 mate_dense_workspace_bytes = _lib.mate_dense_workspace_bytes
 mate_attn_fwd_dense = _lib.mate_attn_fwd_dense
 mate_attn_bwd_dense = _lib.mate_attn_bwd_dense
+mate_qkv_project = _lib.mate_qkv_project
+mate_out_project = _lib.mate_out_project
 
 
 def mate_status_string(status: int) -> str:
@@ -261,6 +268,37 @@ def attn_bwd_dense(q, k, v, out, lse, dout, row_ids, col_ids, flags, head_kind, 
                                _dev(dv, "dv"), ws.data_ptr(), ws.numel(), _stream()),
            "mate_attn_bwd_dense")
     return dq, dk, dv
+
+
+def qkv_project(x, w_qkv, bias, flags, H: int, q=None, k=None, v=None):
+    """x [B,N,E] bf16, w_qkv [3*H*64, E] bf16, bias [3*H*64] float32 or None -> q, k, v [B,H,N,64]."""
+    B, N, E = x.shape
+    assert x.dtype == torch.bfloat16 and w_qkv.dtype == torch.bfloat16 and w_qkv.shape == (3 * H * 64, E)
+    assert flags.dtype == torch.uint8 and flags.shape == (B, N)
+    assert bias is None or (bias.dtype == torch.float32 and bias.shape == (3 * H * 64,))
+    outs = [t if t is not None else torch.empty((B, H, N, 64), dtype=x.dtype, device=x.device) for t in (q, k, v)]
+    for t in outs:
+        assert t.dtype == x.dtype and t.shape == (B, H, N, 64)
+    _check(mate_qkv_project(_dev(x, "x"), _dev(w_qkv, "w_qkv"), _dev(bias, "bias") if bias is not None else None,
+                            _dev(flags, "flags"), B, N, H, E, MATE_BF16, *(_dev(t, "out") for t in outs),
+                            _stream()), "mate_qkv_project")
+    return tuple(outs)
+
+
+def out_project(o, w_o, bias, flags, y=None):
+    """o [B,H,N,64] bf16, w_o [E, H*64] bf16, bias [E] float32 or None -> y [B,N,E]."""
+    B, H, N, D = o.shape
+    E = w_o.shape[0]
+    assert o.dtype == torch.bfloat16 and w_o.dtype == torch.bfloat16 and w_o.shape == (E, H * 64) and D == 64
+    assert flags.dtype == torch.uint8 and flags.shape == (B, N)
+    assert bias is None or (bias.dtype == torch.float32 and bias.shape == (E,))
+    if y is None:
+        y = torch.empty((B, N, E), dtype=o.dtype, device=o.device)
+    assert y.dtype == o.dtype and y.shape == (B, N, E)
+    _check(mate_out_project(_dev(o, "o"), _dev(w_o, "w_o"), _dev(bias, "bias") if bias is not None else None,
+                            _dev(flags, "flags"), B, N, H, E, MATE_BF16, _dev(y, "y"), _stream()),
+           "mate_out_project")
+    return y
 
 
 def prefer_dense(N: int, dtype: torch.dtype = torch.bfloat16) -> bool:

@@ -1,0 +1,128 @@
+"""GPU parity of the projections either side of the attention (bf16 MFMA GEMMs with the head
+split / head gather fused) against the float64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mate_oracle as orc
+from paper_2109_04312_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+P = synth.TOK_PAD
+
+
+def bf16(x):
+    return synth.round_to_bf16(np.asarray(x, np.float32)).astype(np.float32)
+
+
+def dev(x, dtype=torch.bfloat16):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(dtype).cuda()
+
+
+def close(got, want, what):
+    """bf16 output of an fp32-accumulated product: the tolerances of the bf16 attention path."""
+    got = got.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)), what
+    err = np.abs(got - want)
+    rel = float((err / np.maximum(1.0, np.abs(want))).max())
+    mean_rel = float(err.mean() / (np.abs(want).mean() + 1e-3))
+    print(f"   {what}: max-abs rel. to max(1,|ref|) {rel:.2e}, mean-rel {mean_rel:.2e}", flush=True)
+    assert rel <= hp.TOL["bf16"]["max_abs"] and mean_rel <= hp.TOL["bf16"]["mean_rel"], what
+
+
+def make(seed, B, N, H, E, pad_tail=0, scattered_pads=True, bias=True):
+    rng = np.random.default_rng(seed)
+    x = bf16(rng.standard_normal((B, N, E)))
+    w_qkv = bf16(rng.standard_normal((3 * H * 64, E)) / np.sqrt(E))
+    w_o = bf16(rng.standard_normal((E, H * 64)) / np.sqrt(H * 64))
+    b_qkv = rng.standard_normal(3 * H * 64).astype(np.float32) if bias else None
+    b_o = rng.standard_normal(E).astype(np.float32) if bias else None
+    flags = rng.choice([synth.TOK_LOCAL, synth.TOK_GLOBAL], size=(B, N)).astype(np.uint8)
+    if scattered_pads:
+        flags[rng.random((B, N)) < 0.1] = P
+    if pad_tail:
+        flags[:, N - pad_tail:] = P
+    o = bf16(rng.standard_normal((B, H, N, 64)))
+    return x, w_qkv, b_qkv, w_o, b_o, flags, o
+
+
+def check(seed, B, N, H, E, **kw):
+    from paper_2109_04312_amd import mate
+    print(f"projections B={B} N={N} H={H} E={E} {kw}", flush=True)
+    x, w_qkv, b_qkv, w_o, b_o, flags, o = make(seed, B, N, H, E, **kw)
+    nan = lambda *shape: torch.full(shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    fl = torch.from_numpy(flags).cuda()
+    q, k, v = mate.qkv_project(dev(x), dev(w_qkv), None if b_qkv is None else dev(b_qkv, torch.float32), fl, H,
+                               q=nan(B, H, N, 64), k=nan(B, H, N, 64), v=nan(B, H, N, 64))
+    y = mate.out_project(dev(o), dev(w_o), None if b_o is None else dev(b_o, torch.float32), fl, y=nan(B, N, E))
+    torch.cuda.synchronize()
+    want = orc.project_qkv(x, w_qkv, b_qkv, flags, H)
+    for name, g, r in zip("qkv", (q, k, v), want):
+        close(g, r, name)
+        assert bool((g.float().cpu().numpy()[np.broadcast_to((flags == P)[:, None, :, None], r.shape)] == 0).all())
+    close(y, orc.project_out(o, w_o, b_o, flags), "y")
+    assert bool((y.float().cpu().numpy()[flags == P] == 0).all())
+
+
+@pytest.mark.parametrize("N", [1, 64, 127, 128, 129, 200, 333])
+def test_small_ragged(N):
+    check(N, 2, N, 2, 128)
+
+
+def test_no_bias_and_tiles_of_padding_only():
+    check(1, 3, 700, 4, 256, pad_tail=300, bias=False)
+    check(2, 1, 512, 2, 128, pad_tail=512, scattered_pads=False)       # nothing but padding
+
+
+def test_bert_base_shape():
+    check(3, 4, 512, 12, 768, pad_tail=100)
+
+
+def test_headline_shape():
+    # configuration 4's layer: B=2, N=8192, 16 heads, model width 1024
+    check(4, 2, 8192, 16, 1024, pad_tail=1700, scattered_pads=False)
+
+
+def test_layer_forward_end_to_end():
+    """x -> QKV projection -> segment build -> attention -> output projection, every step in the
+    library, against the same chain in the oracle (which keeps float64 between the steps, so the
+    bound is looser than a single step's: three roundings to bf16 on the way)."""
+    from paper_2109_04312_amd import mate
+    w = synth.make_config(2, tensors=False)
+    st = w.structure
+    B, N, H, E = st.B, st.N, 12, 768
+    rng = np.random.default_rng(9)
+    x = bf16(rng.standard_normal((B, N, E)))
+    w_qkv = bf16(rng.standard_normal((3 * H * 64, E)) / np.sqrt(E))
+    w_o = bf16(rng.standard_normal((E, H * 64)) / np.sqrt(H * 64))
+    hk = synth.half_row_half_col(H)
+    r, c, f = hp.dev_structure(st)
+    q, k, v = mate.qkv_project(dev(x), dev(w_qkv), None, f, H)
+    seg = mate.build_segments(r, c, f)
+    o, _ = mate.attn_fwd(q, k, v, seg, hk, 0.125)
+    y = mate.out_project(o, dev(w_o), None, f)
+    torch.cuda.synchronize()
+    for b in (0, 17):
+        sl = slice(b, b + 1)
+        qr, kr, vr = orc.project_qkv(x[sl], w_qkv, None, st.flags[sl], H)
+        orf, _ = orc.attn_forward(qr, kr, vr, st.row_ids[sl], st.col_ids[sl], st.flags[sl], hk, 0.125)
+        yr = orc.project_out(orf, w_o, None, st.flags[sl])
+        got = y[sl].float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - yr)
+        rel = float((err / np.maximum(1.0, np.abs(yr))).max())
+        mean_rel = float(err.mean() / (np.abs(yr).mean() + 1e-3))
+        print(f"   layer b={b}: max {rel:.2e} mean-rel {mean_rel:.2e}", flush=True)
+        assert rel <= 3e-2 and mean_rel <= 1.5e-2
+
+
+def test_unsupported_arguments():
+    from paper_2109_04312_amd import mate
+    x, w_qkv, b_qkv, w_o, b_o, flags, o = make(0, 1, 64, 3, 128, bias=False)
+    with pytest.raises(mate.MateError) as e:        # odd number of heads
+        mate.qkv_project(dev(x), dev(w_qkv), None, torch.from_numpy(flags).cuda(), 3)
+    assert e.value.status == mate.MATE_ERR_UNSUPPORTED
+    x, w_qkv, b_qkv, w_o, b_o, flags, o = make(0, 1, 64, 2, 192, bias=False)
+    with pytest.raises(mate.MateError) as e:        # width not a multiple of 128
+        mate.out_project(dev(o), dev(w_o), None, torch.from_numpy(flags).cuda())
+    assert e.value.status == mate.MATE_ERR_UNSUPPORTED
