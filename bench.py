@@ -136,6 +136,68 @@ def breakeven(steps, warmup):
                       "step": "segment: build + fwd + bwd; dense: fwd + bwd"}))
 
 
+def projections(cfg, steps, warmup):
+    """Times mate_qkv_project and mate_out_project on a configuration's layer shape (model width
+    64 * H) with HIP events recorded by the library around each launch."""
+    import ctypes as C
+    import torch
+    from paper_2109_04312_amd import mate, synth
+    torch.cuda.set_device(0)
+    w = synth.make_config(cfg, tensors=False)
+    st = w.structure
+    B, N, H = st.B, st.N, len(w.head_kind)
+    E = 64 * H
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED)
+    x = torch.randn((B, N, E), device="cuda", generator=g).to(torch.bfloat16)
+    w_qkv = (torch.randn((3 * E, E), device="cuda", generator=g) / E ** 0.5).to(torch.bfloat16)
+    w_o = (torch.randn((E, E), device="cuda", generator=g) / E ** 0.5).to(torch.bfloat16)
+    b_qkv = torch.randn(3 * E, device="cuda", generator=g)
+    b_o = torch.randn(E, device="cuda", generator=g)
+    fl = torch.from_numpy(st.flags).cuda()
+    q, k, v = (torch.empty((B, H, N, 64), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    y = torch.empty((B, N, E), dtype=torch.bfloat16, device="cuda")
+    hip = C.CDLL("libamdhip64.so")
+
+    def new_event():
+        ev = C.c_void_p()
+        assert hip.hipEventCreate(C.byref(ev)) == 0
+        return ev
+
+    def step():
+        mate.qkv_project(x, w_qkv, b_qkv, fl, H, q=q, k=k, v=v)
+        mate.out_project(q, w_o, b_o, fl, y=y)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    both = (time.perf_counter() - t0) / steps
+    res = {}
+    for name, kid in (("qkv_project", mate.MATE_KERNEL_QKV_PROJECT), ("out_project", mate.MATE_KERNEL_OUT_PROJECT)):
+        evs = [(new_event(), new_event()) for _ in range(steps)]
+        for e0, e1 in evs:
+            assert mate.mate_profile_kernel(kid, e0, e1) == 0
+            step()
+        torch.cuda.synchronize()
+        tot = 0.0
+        for e0, e1 in evs:
+            ms = C.c_float()
+            assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
+            tot += ms.value
+        res[name] = tot / steps * 1e-3
+    nonpad = int((st.flags != synth.TOK_PAD).sum())
+    flop = {"qkv_project": 2.0 * nonpad * E * 3 * E, "out_project": 2.0 * nonpad * E * E}
+    out = {"projections": {n: {"us": t * 1e6, "algorithmic_flop": flop[n], "achieved_tflops": flop[n] / t / 1e12,
+                               "frac_of_bf16_mfma_peak": flop[n] / t / 1e12 / PEAK_BF16_TFLOPS} for n, t in res.items()},
+           "workload": w.name, "B": B, "N": N, "H": H, "E": E, "non_pad_tokens": nonpad, "dtype": "bf16",
+           "us_both_wall": both * 1e6, "steps": steps,
+           "flop_convention": "2 * non-pad tokens * K * F (pad rows are not algorithmic work)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +213,8 @@ def main():
     ap.add_argument("--breakeven", action="store_true",
                     help="only time the segment path (build + fwd + bwd) against the dense-mask "
                          "entry points (fwd + bwd) at short sequence lengths and exit")
+    ap.add_argument("--projections", action="store_true",
+                    help="time the QKV and output projection kernels on the configuration's layer shape and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -172,6 +236,10 @@ def main():
 
     if args.breakeven:
         breakeven(args.steps, args.warmup)
+        return
+
+    if args.projections:
+        projections(args.config, args.steps, args.warmup)
         return
 
     w = synth.make_config(args.config)

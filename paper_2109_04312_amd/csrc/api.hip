@@ -291,7 +291,7 @@ mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, con
 }
 
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event) {
-  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_BWD_DKV_DENSE) return MATE_ERR_UNSUPPORTED;
+  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_OUT_PROJECT) return MATE_ERR_UNSUPPORTED;
   if (kernel != MATE_KERNEL_NONE && (!start_event || !stop_event)) return MATE_ERR_NULL;
   g_profile_hook.kernel = kernel;
   g_profile_hook.start = static_cast<hipEvent_t>(start_event);

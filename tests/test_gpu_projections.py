@@ -79,6 +79,12 @@ def test_bert_base_shape():
     check(3, 4, 512, 12, 768, pad_tail=100)
 
 
+def test_large_tiles_ragged_with_scattered_pads():
+    # enough tiles for the 256 x 256 shape of the QKV kernel; N is not a multiple of 256
+    check(5, 9, 1000, 12, 768, pad_tail=120)
+    check(6, 3, 2500, 16, 1024, pad_tail=0)
+
+
 def test_headline_shape():
     # configuration 4's layer: B=2, N=8192, 16 heads, model width 1024
     check(4, 2, 8192, 16, 1024, pad_tail=1700, scattered_pads=False)
