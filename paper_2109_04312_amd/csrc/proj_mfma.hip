@@ -166,17 +166,23 @@ __global__ __launch_bounds__(S::kThreadsP, S::kWaves == 4 ? 2 : 1) void proj_ker
       const char* st = lds + (ks % S::kStages) * S::kStageBytesP;
       const char* tok_t = st + wt * S::kBT * 32 * 128;
       const char* w_t = st + S::kTokTiles * kTileBytes + wf * 64 * 128;
+      // operand fragments are read one 16-wide k slice ahead of the contractions that use them
+      bf16x8 wfrag[2][2], tfrag[2][S::kBT];
+      auto read_slice = [&](int buf, int k16) {
+#pragma unroll
+        for (int bf = 0; bf < 2; ++bf) wfrag[buf][bf] = read_plain(w_t + bf * 32 * 128, poff[k16]);
+#pragma unroll
+        for (int bt = 0; bt < S::kBT; ++bt) tfrag[buf][bt] = read_plain(tok_t + bt * 32 * 128, poff[k16]);
+      };
+      read_slice(0, 0);
 #pragma unroll
       for (int k16 = 0; k16 < 4; ++k16) {
-        bf16x8 wfrag[2], tfrag[S::kBT];
-#pragma unroll
-        for (int bf = 0; bf < 2; ++bf) wfrag[bf] = read_plain(w_t + bf * 32 * 128, poff[k16]);
-#pragma unroll
-        for (int bt = 0; bt < S::kBT; ++bt) tfrag[bt] = read_plain(tok_t + bt * 32 * 128, poff[k16]);
+        if (k16 + 1 < 4) read_slice((k16 + 1) & 1, k16 + 1);
 #pragma unroll
         for (int bf = 0; bf < 2; ++bf)
 #pragma unroll
-          for (int bt = 0; bt < S::kBT; ++bt) acc[bf][bt] = mfma(wfrag[bf], tfrag[bt], acc[bf][bt]);
+          for (int bt = 0; bt < S::kBT; ++bt)
+            acc[bf][bt] = mfma(wfrag[k16 & 1][bf], tfrag[k16 & 1][bt], acc[bf][bt]);
       }
     }
   }
