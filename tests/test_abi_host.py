@@ -73,3 +73,33 @@ def test_argument_errors_are_caught_on_the_host(mate):
     assert b(fake, fake, fake, 1, 0, fake, None) == mate.MATE_ERR_SHAPE
     assert mate.mate_segments_export(None, 1, 128, 0, None, None, None, None, None, None) == mate.MATE_ERR_NULL
     assert mate.mate_segments_export(fake, 1, 128, 2, None, None, None, None, None, None) == mate.MATE_ERR_SHAPE
+
+
+def test_argument_errors_of_the_later_entry_points(mate):
+    fake = 0x1000  # never dereferenced
+    bb = mate.mate_build_segments_bucketed
+    assert bb(fake, fake, None, 1, 128, 116, 42, fake, None) == mate.MATE_ERR_NULL
+    assert bb(fake, fake, fake, 1, 0, 116, 42, fake, None) == mate.MATE_ERR_SHAPE
+    assert bb(fake, fake, fake, 1, 128, -1, 42, fake, None) == mate.MATE_ERR_UNSUPPORTED
+    assert bb(fake, fake, fake, 1, 128, 116, 0, fake, None) == mate.MATE_ERR_UNSUPPORTED
+    assert mate.mate_segments_export_windows(fake, 1, 128, 0, None, None) == mate.MATE_ERR_NULL
+    assert mate.mate_segments_export_windows(fake, 1, 128, 3, fake, None) == mate.MATE_ERR_SHAPE
+    cp = mate.mate_cell_positions
+    assert cp(fake, fake, fake, 1, 128, None, None) == mate.MATE_ERR_NULL
+    assert cp(fake, fake, fake, 1, mate.MATE_MAX_N + 1, fake, None) == mate.MATE_ERR_SHAPE
+    qp = mate.mate_qkv_project
+    ok = [fake, fake, None, fake, 2, 512, 12, 768, mate.MATE_BF16, fake, fake, fake, None]
+    for pos, val, want in ((0, None, mate.MATE_ERR_NULL), (11, None, mate.MATE_ERR_NULL),
+                           (6, 11, mate.MATE_ERR_UNSUPPORTED),      # odd number of heads
+                           (7, 700, mate.MATE_ERR_UNSUPPORTED),     # width not a multiple of 128
+                           (8, mate.MATE_F32, mate.MATE_ERR_UNSUPPORTED), (5, 0, mate.MATE_ERR_SHAPE)):
+        args = list(ok)
+        args[pos] = val
+        assert qp(*args) == want, (pos, val)
+    op = mate.mate_out_project
+    ok = [fake, fake, None, fake, 2, 512, 12, 768, mate.MATE_BF16, fake, None]
+    for pos, val, want in ((1, None, mate.MATE_ERR_NULL), (9, None, mate.MATE_ERR_NULL),
+                           (7, 64, mate.MATE_ERR_UNSUPPORTED), (4, 0, mate.MATE_ERR_SHAPE)):
+        args = list(ok)
+        args[pos] = val
+        assert op(*args) == want, (pos, val)
