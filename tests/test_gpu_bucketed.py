@@ -106,6 +106,29 @@ def test_config6_long_cells_paper_mode_sampled_heads():
     check(synth.make_config(6), PAPER_MODE, pairs=[(0, 0), (0, 8), (5, 3), (7, 15)])
 
 
+@pytest.mark.parametrize("idx", [4, 5])
+def test_full_size_invariants_over_all_heads(idx):
+    """Oracle-free invariants on EVERY (sequence, head) of the full-size configurations in the
+    published models' mode (each softmax row sums to 1 whatever the window; rows of dS sum to 0)."""
+    from paper_2109_04312_amd import mate
+    w = synth.make_config(idx)
+    r, c, f = hp.dev_structure(w.structure)
+    seg = mate.build_segments(r, c, f, bucketed=PAPER_MODE)
+    q, k, v, do = (hp.to_dev(x, "bf16") for x in (w.q, w.k, w.v, w.do))
+    nonpad = (f != synth.TOK_PAD)[:, None, :, None]
+    o1, _ = mate.attn_fwd(q, k, torch.ones_like(v), seg, w.head_kind, w.scale)
+    assert float(((o1.float() - 1.0).abs() * nonpad).max()) <= 4e-3
+    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, w.scale)
+    dq, dk, dv = mate.attn_bwd(q, k, v, out, lse, do, seg, w.head_kind, w.scale)
+    torch.cuda.synchronize()
+    n_tok = nonpad.sum(dim=2).clamp(min=1).float()
+    sum_do = (do.float() * nonpad).sum(dim=2)
+    assert float(((dv.float().sum(dim=2) - sum_do).abs() / n_tok.sqrt()).max()) <= 8e-3
+    scale_k = dk.float().abs().sum(dim=2).clamp(min=1e-3)
+    assert float((dk.float().sum(dim=2).abs() / scale_k).max()) <= 8e-3
+    assert bool(torch.isfinite(dq.float()).all())
+
+
 def test_bad_arguments():
     from paper_2109_04312_amd import mate
     w = synth.make_config(1, tensors=False)
