@@ -82,7 +82,8 @@ size_t mate_workspace_bytes(int B, int H, int N, int D, mate_dtype t, int for_bw
  *
  *   row_ids, col_ids  [B, N] int32, >= 0 for LOCAL tokens
  *   flags             [B, N] uint8, MATE_TOK_*
- *   segments          mate_segments_bytes(B, N) bytes; every table in it is overwritten
+ *   segments          mate_segments_bytes(B, N) bytes; the valid part of every table is
+ *                     overwritten (entries past a list's length are left as they were)
  *
  * Asynchronous on `stream`.  A negative id on a LOCAL token or a flag > 2 does not stop the
  * build (the id is ordered as an unsigned number, the token is treated as padding) but sets

@@ -146,6 +146,11 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
   int bad = 0;
   for (int b = 0; b < B; ++b) {
     const int* c = head.data() + kHdrWords + (size_t)b * kCountWords;
+    // the builder writes the valid part of each list only: the rest is -1 by this function's contract
+    if (perm) std::fill(perm + (size_t)b * N + c[C_L], perm + (size_t)(b + 1) * N, -1);
+    if (global_idx) std::fill(global_idx + (size_t)b * N + c[C_G], global_idx + (size_t)(b + 1) * N, -1);
+    if (seg_off)
+      std::fill(seg_off + (size_t)b * (N + 1) + c[C_SROW + view] + 1, seg_off + (size_t)(b + 1) * (N + 1), -1);
     if (counts) {
       counts[3 * b + 0] = c[C_G];
       counts[3 * b + 1] = c[C_L];

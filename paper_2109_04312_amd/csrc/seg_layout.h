@@ -4,12 +4,12 @@
 //   hdr[16]            magic, B, N, 0, global-part limit and radius of the bucketed mode (N and 0
 //                      without it), rest 0
 //   counts[B][12]      G, L, P (pad count), S_row, S_col, bad ids seen (rows, cols), rest 0
-//   global_idx[B][N]   ascending positions of GLOBAL tokens, -1 past G
-//   pad_idx[B][N]      ascending positions of PAD tokens, -1 past P
+//   global_idx[B][N]   ascending positions of GLOBAL tokens; entries past G are not written
+//   pad_idx[B][N]      ascending positions of PAD tokens; entries past P are not written
 //   gunit[B][T][8]     work units of question-token owners (T = ceil(N / 128)), see below
 //   per view v (0 rows, 1 columns):
-//     perm[B][N]         sorted slot -> token position, -1 past L
-//     seg_off[B][N+1]    first slot of each segment, L at index S, -1 past that
+//     perm[B][N]         sorted slot -> token position; entries past L are not written
+//     seg_off[B][N+1]    first slot of each segment, L at index S; nothing written past that
 //     seg_of_tok[B][N]   token position -> segment index, -1 for GLOBAL / PAD
 //     slot_rng[B][N][2]  per sorted slot: [first slot, one-past-last slot) of its window = its
 //                        segment, in bucketed mode cut to its own and the two adjacent buckets

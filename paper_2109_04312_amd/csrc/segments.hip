@@ -218,8 +218,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     p_at += __popcll(mp);
   }
   if (view == 0) {
-    for (int i = G + tid; i < N; i += kSegThreads) global_idx[i] = -1;
-    for (int i = P + tid; i < N; i += kSegThreads) pad_idx[i] = -1;
+    // entries past G and P stay unwritten: nothing reads them (the export hook masks them)
     if (tid == 0) { counts[C_G] = G; counts[C_L] = L; counts[C_P] = P; }
   }
   if (tid == 0) counts[5 + view] = s_bad;
@@ -317,13 +316,10 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
       seg_of_tok[my_pos[e]] = seg_idx;
       seg_of_slot[s] = (unsigned short)seg_idx;
       if (head) { seg_start[seg_idx] = (unsigned short)s; seg_off[seg_idx] = s; }
-    } else if (s < N) {
-      perm[s] = -1;
-    }
+    }  // perm past L, like seg_off past S, stays unwritten (masked by the export hook)
     seg_at += __popcll(mh);
   }
   if (tid == 0) { seg_off[S] = L; counts[C_SROW + view] = S; }
-  for (int i = S + 1 + tid; i <= N; i += kSegThreads) seg_off[i] = -1;
   lds_barrier();
   // window of slot s: its segment, in bucketed mode cut to the neighbouring buckets.  Slots are
   // below 2^14, so the bucket index comes exactly from one float multiply: (s + 0.5) / radius is

@@ -67,19 +67,31 @@ def test_segments_bad_ids_reported():
 
 
 def test_segments_rebuild_is_deterministic_and_reusable():
+    """The builder writes the valid part of every list only, so determinism is checked on
+    zero-filled buffers, and reuse in place (stale entries of another batch behind the valid
+    parts) through the exported tables and through the attention kernels' results."""
     from paper_2109_04312_amd import mate
     rng = np.random.default_rng(3)
     st1 = synth.random_structure(rng, 4, 777, max_rows=50, max_cols=9, scatter=True)
     st2 = synth.random_structure(rng, 4, 777, max_rows=20, max_cols=3)
-    seg = _build(st1)
-    a = seg.buf.clone()
-    r, c, f = hp.dev_structure(st2)
-    mate.build_segments(r, c, f, out=seg)     # overwrite in place with another batch
-    hp.compare_segments(seg, st2)
-    r, c, f = hp.dev_structure(st1)
-    mate.build_segments(r, c, f, out=seg)
+    nbytes = mate.mate_segments_bytes(4, 777)
+    zeroed = lambda: mate.Segments(torch.zeros(nbytes, dtype=torch.uint8, device="cuda"), 4, 777)
+    r1, c1, f1 = hp.dev_structure(st1)
+    a = mate.build_segments(r1, c1, f1, out=zeroed())
+    b = mate.build_segments(r1, c1, f1, out=zeroed())
     torch.cuda.synchronize()
-    assert torch.equal(seg.buf, a)
+    assert torch.equal(a.buf, b.buf)
+    q, k, v, _ = (hp.to_dev(x, "bf16") for x in synth.draw_tensors(rng, 4, 2, 777, 64, "bf16", 4))
+    hk = np.array([synth.HEAD_ROW, synth.HEAD_COL], np.uint8)
+    want = mate.attn_fwd(q, k, v, a, hk, 0.125)
+    r2, c2, f2 = hp.dev_structure(st2)
+    mate.build_segments(r2, c2, f2, out=a)     # overwrite in place with another batch
+    hp.compare_segments(a, st2)
+    mate.build_segments(r1, c1, f1, out=a)     # and back
+    hp.compare_segments(a, st1)
+    got = mate.attn_fwd(q, k, v, a, hk, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
 
 
 def _positions(st):
