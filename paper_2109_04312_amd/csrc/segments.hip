@@ -132,14 +132,24 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   // and ranks inside a batch come from ballots.
   const int w0 = wave * CHUNK;
 
+  // All of this wavefront's inputs first, in one go: the loads travel together instead of one
+  // dependent round trip per batch (the compiler does not move them across the stores below).
+  unsigned char in_flag[NB];
+  int in_id[NB];
+#pragma unroll
+  for (int e = 0; e < NB; ++e) {
+    const int i = w0 + e * 64 + lane;
+    in_flag[e] = i < N ? fl[i] : (unsigned char)3;
+    in_id[e] = i < N ? id_src[i] : 0;
+  }
+
   // ---- bucketed mode: question tokens past the first max_global join the table tokens ----------
   unsigned demote = 0;  // bit e: my element of batch e is such a token
   if (max_global < N) {  // uniform; a sequence has at most N question tokens
     int n_q = 0;
 #pragma unroll
     for (int e = 0; e < NB; ++e) {
-      const int i = w0 + e * 64 + lane;
-      n_q += __popcll(__ballot(i < N && fl[i] == 1));
+      n_q += __popcll(__ballot(in_flag[e] == 1));
     }
     if (lane == 0) wave_tot[1][wave] = n_q;
     lds_barrier();
@@ -150,8 +160,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     lds_barrier();  // wave_tot is written again below
 #pragma unroll
     for (int e = 0; e < NB; ++e) {
-      const int i = w0 + e * 64 + lane;
-      const bool is_q = i < N && fl[i] == 1;
+      const bool is_q = in_flag[e] == 1;
       const unsigned long long mq = __ballot(is_q);
       if (is_q && q_at + lanes_before(mq) >= max_global) demote |= 1u << e;
       q_at += __popcll(mq);
@@ -166,10 +175,10 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     const int i = w0 + e * 64 + lane;
     unsigned char f = 3;
     if (i < N) {
-      f = fl[i];
+      f = in_flag[e];
       if (f > 2) { bad = 1; f = 2; }
       if ((demote >> e) & 1u) f = 0;
-      const int id = id_src[i];  // loaded for every position so that it does not wait for the flag
+      const int id = in_id[e];
       if (f == 0) {
         if (id < 0) bad = 1;
         ids[i] = id;
