@@ -66,8 +66,8 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   TileStream<kDqStage, kDqNS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
   stream.begin();
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
-  if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
-  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi), "v"(me.stage_tok));  // the owned rows are known from here on
+  if (tid < BM) q_tok[tid] = me.stage_tok;
   stream.prime();
 
   // this lane's query row and dO row as B operands (column m, k = dims), and delta
@@ -213,8 +213,8 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
   stream.begin();
   // `me` is this lane's key; its window is the set of query slots that see it
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
-  if (tid < BM) k_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
-  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi), "v"(me.stage_tok));  // the owned rows are known from here on
+  if (tid < BM) k_tok[tid] = me.stage_tok;
   stream.prime();
 
   bf16x8 kf[4], vf[4];  // this lane's key and value rows as B operands

@@ -69,8 +69,8 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   TileStream<kStageBytes, NS> stream(u, global_idx, lds, idx_ring, K, V, nullptr, 0, wave, lane);
   stream.begin();
   const OwnedRow me = owned_row(u, a, b, view, wave, m);
-  if (tid < BM) q_tok[tid] = u.t0 + tid < u.own_count ? u.own_list[u.t0 + tid] : -1;
-  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi));  // the owned rows are known from here on
+  asm volatile("" ::"v"(me.pos), "v"(me.lo), "v"(me.hi), "v"(me.stage_tok));  // the owned rows are known from here on
+  if (tid < BM) q_tok[tid] = me.stage_tok;
   stream.prime();
 
   bf16x8 qf[4];

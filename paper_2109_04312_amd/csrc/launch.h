@@ -19,7 +19,8 @@ struct AttnArgs {
   float* part_ml;           // forward: running max (log2 domain) and sum per partial row
   SegTables seg;
   unsigned char head_kind[256];
-  unsigned char head_order[256];  // heads sorted column heads first (stable)
+  alignas(4) unsigned char head_order[256];  // heads sorted column heads first (stable);
+                                             // read as 32-bit words by the kernels
   int n_col;                      // number of column heads
   int B, H, N;
   float scale;

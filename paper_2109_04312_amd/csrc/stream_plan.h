@@ -58,6 +58,14 @@ inline int unit_grid(int B, int H, int N, int n_col) {
   return 8 * ((nc + nr) * (T + 2) + (nc + nr) * T);
 }
 
+// Entry i of the head order.  A byte indexed by a run-time value would be fetched with a vector
+// load (a memory round trip at the start of every workgroup); the containing 32-bit word comes
+// through the scalar cache with the other kernel arguments.
+__device__ inline int head_at(const AttnArgs& a, int i) {
+  const unsigned word = reinterpret_cast<const unsigned*>(a.head_order)[i >> 2];
+  return (word >> (8 * (i & 3))) & 0xffu;
+}
+
 // Returns false if this workgroup has nothing to do.  Everything here is wave-uniform and
 // stays in scalar registers.
 __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
@@ -103,12 +111,12 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   if (j < nc) {
     const int c = q + 8 * j;
     b = c / n_col;
-    h = a.head_order[c % n_col];
+    h = head_at(a, c % n_col);
     w.view = 1;
   } else {
     const int r = qr + 8 * (j - nc);
     b = r / n_row;
-    h = a.head_order[n_col + r % n_row];
+    h = head_at(a, n_col + r % n_row);
     w.view = 0;
   }
   w.bh = b * a.H + h;
@@ -146,6 +154,8 @@ __device__ inline void tile_source(const UnitPlan& u, const int* global_idx, int
 
 // Per-lane view of the owned row: position, and the streamed-slot window it may meet.
 struct OwnedRow {
+  int stage_tok;      // token position of owned row threadIdx.x (-1 past the end or past row 127):
+                      // what the epilogue's row table holds, fetched together with `pos`
   int pos;            // token position (rows past the end repeat the last valid one)
   bool valid;
   int lo, hi;         // this row's window of streamed table slots
@@ -161,6 +171,10 @@ __device__ inline OwnedRow owned_row(const UnitPlan& u, const AttnArgs& a, int b
   r.valid = slot_raw < u.own_count;
   r.wave_active = u.t0 + wave * 32 < u.own_count;
   r.pos = u.own_list[slot];
+  {
+    const int row = u.t0 + (int)threadIdx.x;
+    r.stage_tok = threadIdx.x < BM && row < u.own_count ? u.own_list[row] : -1;
+  }
   r.lo = 0;
   r.hi = u.L;
   if (u.kind == UNIT_LOCAL) {
