@@ -331,20 +331,24 @@ __global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(AttnArgs a) {
   for (int x = blockIdx.x * 32 + (threadIdx.x >> 3); x < G; x += gridDim.x * 32) {
   const int gt = x / BM, r = x % BM;
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
-  // chunks are read sixteen at a time so that their loads overlap; the order of the additions
-  // is fixed, so the result is deterministic
+  // chunks are read eight at a time, all loads issued before the first addition (the pin below:
+  // left alone, the compiler keeps only a few in flight and the kernel becomes a chain of memory
+  // round trips); the order of the additions is fixed, so the result is deterministic
   const int tok = a.seg.global_idx[(size_t)b * N + x];
-  constexpr int kBatch = 16;
+  constexpr int kBatch = 8;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c0 = 0; c0 < s.n_chunks; c0 += kBatch) {
-    float4 p0[kBatch], p1[kBatch];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 p0[kBatch], p1[kBatch];
 #pragma unroll
     for (int e = 0; e < kBatch; ++e) {
       const int c = min(c0 + e, s.n_chunks - 1);
       const float* p = a.part[which] + ((slot0 + c) * BM + r) * kD + piece * 8;
-      p0[e] = *reinterpret_cast<const float4*>(p);
-      p1[e] = *reinterpret_cast<const float4*>(p + 4);
+      p0[e] = *reinterpret_cast<const f32x4*>(p);
+      p1[e] = *reinterpret_cast<const f32x4*>(p + 4);
     }
+    asm volatile("" ::"v"(p0[0]), "v"(p0[1]), "v"(p0[2]), "v"(p0[3]), "v"(p0[4]), "v"(p0[5]), "v"(p0[6]), "v"(p0[7]),
+                 "v"(p1[0]), "v"(p1[1]), "v"(p1[2]), "v"(p1[3]), "v"(p1[4]), "v"(p1[5]), "v"(p1[6]), "v"(p1[7]));
 #pragma unroll
     for (int e = 0; e < kBatch; ++e) {
       const float w = c0 + e < s.n_chunks ? 1.f : 0.f;

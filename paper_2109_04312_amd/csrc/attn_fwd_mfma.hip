@@ -205,22 +205,29 @@ __global__ __launch_bounds__(kThreads) void fwd_finalize_kernel(AttnArgs a) {
   const int gt = x / BM, r = x % BM;
   const int tok = a.seg.global_idx[(size_t)b * N + x];
   const size_t slot0 = (size_t)bh_i * owner_slots(N) + (size_t)gt * s.n_chunks;
-  // Chunks are read kBatch at a time so that their loads overlap (the chunk count is only known
-  // on the device); the combination order is fixed, so the result is deterministic.  A first
-  // batch usually covers every chunk: then each partial is read exactly once.
-  constexpr int kBatch = 16;
+  // Chunks are read kBatch at a time with all loads of a batch issued before the first use (the
+  // pin at the end of load_batch: left alone, the compiler keeps only a few in flight and the
+  // kernel becomes a chain of memory round trips).  The chunk count is only known on the device;
+  // the combination order is fixed, so the result is deterministic.  A first batch usually
+  // covers every chunk: then each partial is read exactly once.
+  constexpr int kBatch = 8;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
   float m = -INFINITY;
-  float2 ml[kBatch];
-  float4 p0[kBatch], p1[kBatch];
+  f32x2 ml[kBatch];
+  f32x4 p0[kBatch], p1[kBatch];
   auto load_batch = [&](int c0) {
 #pragma unroll
     for (int e = 0; e < kBatch; ++e) {
       const int c = min(c0 + e, s.n_chunks - 1);
-      ml[e] = *reinterpret_cast<const float2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
+      ml[e] = *reinterpret_cast<const f32x2*>(a.part_ml + ((slot0 + c) * BM + r) * 2);
       const float* p = a.part[0] + ((slot0 + c) * BM + r) * kD + piece * 8;
-      p0[e] = *reinterpret_cast<const float4*>(p);
-      p1[e] = *reinterpret_cast<const float4*>(p + 4);
+      p0[e] = *reinterpret_cast<const f32x4*>(p);
+      p1[e] = *reinterpret_cast<const f32x4*>(p + 4);
     }
+    asm volatile("" ::"v"(p0[0]), "v"(p0[1]), "v"(p0[2]), "v"(p0[3]), "v"(p0[4]), "v"(p0[5]), "v"(p0[6]), "v"(p0[7]),
+                 "v"(p1[0]), "v"(p1[1]), "v"(p1[2]), "v"(p1[3]), "v"(p1[4]), "v"(p1[5]), "v"(p1[6]), "v"(p1[7]),
+                 "v"(ml[0]), "v"(ml[1]), "v"(ml[2]), "v"(ml[3]), "v"(ml[4]), "v"(ml[5]), "v"(ml[6]), "v"(ml[7]));
   };
   load_batch(0);
 #pragma unroll
