@@ -35,22 +35,26 @@ __global__ __launch_bounds__(kPosThreads) void cell_positions_kernel(
   const int w0 = wave * nb * 64;
   int start[kPosMaxBatches];        // latest cell start at or before my element, inside my wavefront's block
   unsigned char kind[kPosMaxBatches];
+  // All inputs of the wavefront's block first, so that the loads travel together.  The previous
+  // position's values are loaded rather than shuffled: the first lane's neighbour belongs to
+  // another batch or wavefront.
+  bool head[kPosMaxBatches];
+#pragma unroll
+  for (int e = 0; e < kPosMaxBatches; ++e) {
+    if (e >= nb) continue;  // uniform; the loops are fully unrolled so that the arrays stay in registers
+    const int i = w0 + e * 64 + lane;
+    const int ic = min(i, N - 1), ip = max(ic - 1, 0);
+    const unsigned char f = fl[ic], fp = fl[ip];
+    const int r = row[ic], rp = row[ip], c = col[ic], cp = col[ip];
+    kind[e] = i < N ? f : (unsigned char)2;
+    head[e] = i < N && f == 0 && (i == 0 || fp != 0 || rp != r || cp != c);
+  }
   int carry = -1;
 #pragma unroll
   for (int e = 0; e < kPosMaxBatches; ++e) {
-    if (e >= nb) continue;  // uniform; the loop is fully unrolled so that start[] stays in registers
+    if (e >= nb) continue;
     const int i = w0 + e * 64 + lane;
-    unsigned char f = 2;
-    bool head = false;
-    if (i < N) {
-      f = fl[i];
-      if (f == 0) {
-        // the previous position's values are loaded rather than shuffled: the first lane's
-        // neighbour belongs to another batch or wavefront
-        head = i == 0 || fl[i - 1] != 0 || row[i - 1] != row[i] || col[i - 1] != col[i];
-      }
-    }
-    int s = head ? i : -1;
+    int s = head[e] ? i : -1;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       const int up = __shfl_up(s, d, 64);
@@ -59,7 +63,6 @@ __global__ __launch_bounds__(kPosThreads) void cell_positions_kernel(
     s = max(s, carry);
     carry = __shfl(s, 63, 64);
     start[e] = s;
-    kind[e] = f;
   }
   if (lane == 0) wave_last[wave] = carry;
   __syncthreads();
