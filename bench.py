@@ -31,9 +31,9 @@ D = 64
 # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0, the factors a plain copy of known size gives;
 # summaries under profiles/); a kernel or workload that is not listed reports null
 TRAFFIC = {"cfg4_B2_N8192_H16": {
-    "fwd_mfma_kernel": {"fetch_bytes": 62762 * 2048, "write_bytes": 41683 * 1024},
-    "bwd_dq_mfma_kernel": {"fetch_bytes": 91540 * 2048, "write_bytes": 41523 * 1024},
-    "bwd_dkv_mfma_kernel": {"fetch_bytes": 81573 * 2048, "write_bytes": 79375 * 1024},
+    "fwd_mfma_kernel": {"fetch_bytes": 62818 * 2048, "write_bytes": 41672 * 1024},
+    "bwd_dq_mfma_kernel": {"fetch_bytes": 91538 * 2048, "write_bytes": 41572 * 1024},
+    "bwd_dkv_mfma_kernel": {"fetch_bytes": 81600 * 2048, "write_bytes": 79383 * 1024},
 }}
 
 
