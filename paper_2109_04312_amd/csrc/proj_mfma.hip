@@ -87,9 +87,15 @@ __global__ __launch_bounds__(S::kThreadsP, S::kWaves == 4 ? 2 : 1) void proj_ker
   }
   const unsigned char* fl = a.flags + (size_t)b * a.N + n0;
 
-  // a tile of padding only: zeros, no arithmetic
+  // a tile of padding only: zeros, no arithmetic.  The flags stay in LDS for the epilogue (read
+  // from global memory there, every store would wait for a flag load and for the store before it).
+  __shared__ unsigned char tok_flag[kTokRows];
   int any = 0;
-  for (int r = tid; r < rows_valid; r += S::kThreadsP) any |= fl[r] != 2;
+  for (int r = tid; r < rows_valid; r += S::kThreadsP) {
+    const unsigned char f = fl[r];
+    tok_flag[r] = f;
+    any |= f != 2;
+  }
   any = __syncthreads_or(any);
 
   // ---- operand streams ------------------------------------------------------------------
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(S::kThreadsP, S::kWaves == 4 ? 2 : 1) void proj_ker
       const int r = (wt * S::kBT + bt) * 32 + row;  // token row inside the workgroup tile
       if (r < rows_valid) {
         uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((piece ^ (row & 7)) << 4));
-        if (fl[r] == 2) v = make_uint4(0, 0, 0, 0);
+        if (tok_flag[r] == 2) v = make_uint4(0, 0, 0, 0);
         *reinterpret_cast<uint4*>(dst + (size_t)r * dst_stride + piece * 8) = v;
       }
     }
