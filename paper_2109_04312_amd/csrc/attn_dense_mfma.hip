@@ -77,8 +77,10 @@ __device__ inline DenseRow dense_row(const DenseArgs& a, const DenseUnit& u, con
 
 // May the owned row (code mc, global flag) meet a streamed row with code kc?  (Pad owners get
 // arbitrary answers; their results are replaced by zeros.)
+// Written with bitwise operators on purpose: as a conditional expression it compiled to a
+// divergent branch per element.
 __device__ inline bool allowed(int kc, int mc, bool owner_global) {
-  return owner_global ? kc > -2 : (kc == mc) | (kc == -1);
+  return ((int)(kc == mc) | (int)(kc == -1) | ((int)owner_global & (int)(kc > -2))) != 0;
 }
 
 // Streams the sequence's 64-position tiles of two tensors through two LDS stages.
