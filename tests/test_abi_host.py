@@ -103,3 +103,24 @@ def test_argument_errors_of_the_later_entry_points(mate):
         args = list(ok)
         args[pos] = val
         assert op(*args) == want, (pos, val)
+
+
+def test_bench_pair_count_matches_the_oracle():
+    """bench.py counts useful (query, key) pairs with its own vectorised formula (it may not use
+    the oracle outside its cpu_baseline leg); here that bookkeeping is held against the oracle's
+    mask, in both modes."""
+    import importlib.util
+    from oracle import mate_oracle as orc
+    from paper_2109_04312_amd import synth
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    rng = np.random.default_rng(21)
+    for scatter in (False, True):
+        st = synth.random_structure(rng, 4, 150, max_rows=6, max_cols=4, max_global=25, max_cell=9, scatter=scatter)
+        for mode in (None, (7, 3), (0, 1), (100, 50)):
+            got = bench.useful_pairs_per_view(st, mode)
+            for b in range(st.B):
+                for v, kind in enumerate((synth.HEAD_ROW, synth.HEAD_COL)):
+                    want = orc.useful_pairs(st.row_ids[b], st.col_ids[b], st.flags[b], kind, bucketed=mode)
+                    assert got[b, v] == want, (scatter, mode, b, v)
