@@ -197,3 +197,48 @@ def test_argument_errors_leave_outputs_untouched():
     assert st == mate.MATE_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert bool((out == 7).all()) and bool((lse == 7).all())
+
+
+def test_step_replays_identically_from_a_captured_graph():
+    """The library allocates nothing, clears nothing with memsets and never synchronises inside
+    build / forward / backward, so a whole step can be captured once and replayed: every replay
+    (with eager work in between) must reproduce the eager result bit for bit."""
+    from paper_2109_04312_amd import mate
+    w = small_workload(21, "bf16", B=2, N=900, H=4, max_rows=30, max_cols=6, max_global=80, max_cell=6)
+    r, c, f = hp.dev_structure(w.structure)
+    q, k, v, do = (hp.to_dev(x, "bf16") for x in (w.q, w.k, w.v, w.do))
+    B, H, N, D = q.shape
+    code = mate.MATE_BF16
+
+    def buffers():
+        seg = mate.Segments(torch.zeros(mate.mate_segments_bytes(B, N), dtype=torch.uint8, device="cuda"), B, N)
+        return dict(seg=seg, out=torch.empty_like(q), lse=torch.empty((B, H, N), dtype=torch.float32, device="cuda"),
+                    dq=torch.empty_like(q), dk=torch.empty_like(q), dv=torch.empty_like(q),
+                    ws_f=mate.workspace(B, H, N, D, code, False, "cuda"), ws_b=mate.workspace(B, H, N, D, code, True, "cuda"))
+
+    def step(bf):
+        mate.build_segments(r, c, f, out=bf["seg"])
+        mate.attn_fwd(q, k, v, bf["seg"], w.head_kind, w.scale, out=bf["out"], lse=bf["lse"], ws=bf["ws_f"])
+        mate.attn_bwd(q, k, v, bf["out"], bf["lse"], do, bf["seg"], w.head_kind, w.scale,
+                      dq=bf["dq"], dk=bf["dk"], dv=bf["dv"], ws=bf["ws_b"])
+
+    eager, graphed = buffers(), buffers()
+    step(eager)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(graphed)                                  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(graphed)
+    for replay in range(3):
+        for name in ("out", "lse", "dq", "dk", "dv"):
+            graphed[name].fill_(float("nan"))          # a replay must rewrite everything
+        step(eager)                                     # eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("out", "lse", "dq", "dk", "dv"):
+            assert torch.equal(graphed[name], eager[name]), (replay, name)
