@@ -125,6 +125,42 @@ def draw_tensors(rng: np.random.Generator, B, H, N, D, dtype: str, n: int, data_
     return out
 
 
+def draw_wide_range_tensors(rng: np.random.Generator, st: "Structure", H: int, D: int, dtype: str,
+                            sigma_raw: float = 60.0, outliers=(150.0, 200.0, 250.0, 300.0, 350.0),
+                            quantiles=(0.45, 0.6, 0.75, 0.9, 0.97)):
+    """Q, K, V, dO whose raw scores q.k span a wide range (an input recipe only; no attention
+    arithmetic): Q and K are N(0,1) scaled so that q.k has standard deviation `sigma_raw`; the
+    key norms grow with the token's rank among the non-pad positions (factor 0.3 .. 1.7); and a
+    few table tokens, at the given quantiles of the table tokens of each sequence, carry a key
+    that scores about `outliers[i]` more than the rest against every query (all queries share a
+    component of 10 along one random unit direction u, the outlier keys get outliers[i] / 10
+    along u).  V and dO are plain N(0,1).  Returns q, k, v, do as float32 holding dtype-
+    representable values, [B,H,N,D]."""
+    B, N = st.flags.shape
+    c = float(np.sqrt(sigma_raw / np.sqrt(D)))
+    q, k, v, do = (rng.standard_normal((B, H, N, D), dtype=np.float32) for _ in range(4))
+    q *= np.float32(c)
+    k *= np.float32(c)
+    u = rng.standard_normal(D)
+    u = (u / np.linalg.norm(u)).astype(np.float32)
+    q += np.float32(10.0) * u
+    for b in range(B):
+        nonpad = np.flatnonzero(st.flags[b] != TOK_PAD)
+        if len(nonpad):
+            growth = np.ones(N, np.float32)
+            growth[nonpad] = 0.3 + 1.4 * np.arange(len(nonpad), dtype=np.float32) / max(1, len(nonpad) - 1)
+            k[b] *= growth[None, :, None]
+        table = np.flatnonzero(st.flags[b] == TOK_LOCAL)
+        for amount, qt in zip(outliers, quantiles):
+            if len(table):
+                pos = table[min(len(table) - 1, int(qt * len(table)))]
+                k[b, :, pos, :] += np.float32(amount / 10.0) * u
+    out = [q, k, v, do]
+    if dtype == "bf16":
+        out = [round_to_bf16(x) for x in out]
+    return out
+
+
 CONFIG_NAMES = {
     1: "cfg1_tiny_f32_B1_N128_H4",
     2: "cfg2_B32_N512_H12",

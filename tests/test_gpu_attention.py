@@ -1,4 +1,6 @@
 """GPU parity: forward and backward vs the float64 oracle, element by element, through the C ABI."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -22,10 +24,11 @@ def check_workload(w, backward, pairs=None, label=""):
     print(f"case {label or w.name} dtype={w.dtype} shape={w.shape} bwd={backward}", flush=True)
     got, seg = hp.run_hip(w, backward)
     hp.compare_segments(seg, w.structure)
+    t0 = time.perf_counter()
     ref = hp.run_oracle(w, backward, pairs)
+    print(f"   oracle: {len(ref)} (sequence, head) pairs in {time.perf_counter() - t0:.1f} s", flush=True)
     worst = hp.compare(got, ref, w, label or w.name)
-    print("   worst (max-abs rel. to max(1,|ref|), mean-rel):",
-          {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in worst.items()}, flush=True)
+    print(hp.report(worst), flush=True)
 
 
 def test_config1_tiny_f32_forward():
@@ -98,28 +101,36 @@ def test_config2_bf16_fwd_bwd():
 
 
 def test_config3_bf16_fwd_bwd():
+    # 64 of the 128 (sequence, head) pairs: every sequence, four row heads and four column heads
     w = synth.make_config(3)
-    pairs = [(b, h) for b in (0, 5) for h in (0, 7, 8, 15)]
+    pairs = [(b, h) for b in range(8) for h in (0, 1, 6, 7, 8, 9, 14, 15)]
     check_workload(w, backward=True, pairs=pairs)
 
 
-def test_config4_headline_sampled_heads():
-    # Full benchmark size, the launch configuration bench.py times; the oracle evaluates a
-    # sample of (sequence, head) pairs completely (a row head and a column head per sequence).
+@pytest.mark.parametrize("b,kind", [(0, ROW), (0, COL), (1, ROW), (1, COL)])
+def test_config4_headline_every_head(b, kind):
+    # Full benchmark size, the launch configuration bench.py times: every one of the 32
+    # (sequence, head) pairs is compared with the oracle element by element, eight per test (one
+    # sequence's row heads or column heads; the oracle takes 1.5 - 6 s per pair at this length).
     w = synth.make_config(4)
-    check_workload(w, backward=True, pairs=[(0, 0), (0, 15), (1, 7), (1, 8)])
+    pairs = [(b, h) for h in range(16) if w.head_kind[h] == kind]
+    assert len(pairs) == 8
+    check_workload(w, backward=True, pairs=pairs, label=f"{w.name} b={b} kind={kind}")
 
 
 def test_config5_ragged_sampled_heads():
-    w = synth.make_config(5)
+    # every sequence with one row head and one column head (32 of the 256 pairs);
     # b=0: one-row table (row heads dense), b=1: one-column table (column heads dense)
-    check_workload(w, backward=True, pairs=[(0, 0), (0, 8), (1, 3), (1, 12), (9, 1), (15, 14)])
+    w = synth.make_config(5)
+    pairs = [(b, h) for b in range(16) for h in (b % 8, 8 + (3 * b) % 8)]
+    check_workload(w, backward=True, pairs=pairs)
 
 
 def test_config6_long_cells_sampled_heads():
-    # long expanded cells: both views have segments of hundreds of tokens
+    # long expanded cells: both views have segments of hundreds of tokens; every sequence, two
+    # row heads and two column heads (32 of the 128 pairs)
     w = synth.make_config(6)
-    check_workload(w, backward=True, pairs=[(0, 0), (0, 8), (3, 5), (7, 15)])
+    check_workload(w, backward=True, pairs=[(b, h) for b in range(8) for h in (0, 5, 8, 15)])
 
 
 @pytest.mark.parametrize("idx", [4, 5])
@@ -197,6 +208,69 @@ def test_argument_errors_leave_outputs_untouched():
     assert st == mate.MATE_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert bool((out == 7).all()) and bool((lse == 7).all())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tables_of_another_shape_leave_outputs_untouched(dtype):
+    """The attention calls are asynchronous and cannot return what only the device sees: given a
+    table buffer that was built for another (B, N), or never built, every workgroup leaves before
+    using it, the outputs stay as they were, and mate_segments_status names the problem."""
+    from paper_2109_04312_amd import mate
+    w = small_workload(31, dtype, B=2, N=300, H=2, max_rows=9, max_cols=4, max_global=12)
+    r, c, f = hp.dev_structure(w.structure)
+    q, k, v, do = (hp.to_dev(x, dtype) for x in (w.q, w.k, w.v, w.do))
+    B, H, N, D = q.shape
+    code = mate.MATE_BF16 if dtype == "bf16" else mate.MATE_F32
+    hk = np.ascontiguousarray(w.head_kind)
+    nbytes = max(mate.mate_segments_bytes(B, N), mate.mate_segments_bytes(1, 200))
+    other = mate.Segments(torch.zeros(nbytes, dtype=torch.uint8, device="cuda"), 1, 200)
+    mate.build_segments(r[:1, :200].contiguous(), c[:1, :200].contiguous(), f[:1, :200].contiguous(), out=other)
+    never = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")
+    good = mate.build_segments(r, c, f)
+    assert mate.segments_status(good) == mate.MATE_OK
+    assert mate.mate_segments_status(other.buf.data_ptr(), B, N, None) == mate.MATE_ERR_SHAPE
+    assert mate.mate_segments_status(never.data_ptr(), B, N, None) == mate.MATE_ERR_SHAPE
+    out_ref, lse_ref = mate.attn_fwd(q, k, v, good, hk, 0.125)
+    ws_f = mate.workspace(B, H, N, D, code, False, "cuda")
+    ws_b = mate.workspace(B, H, N, D, code, True, "cuda")
+    for buf in (other.buf, never):
+        out = torch.full_like(q, 7.0)
+        lse = torch.full((B, H, N), 7.0, device="cuda")
+        grads = [torch.full_like(q, 7.0) for _ in range(3)]
+        st = mate.mate_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), buf.data_ptr(), hk.ctypes.data,
+                                B, H, N, D, code, 0.125, out.data_ptr(), lse.data_ptr(),
+                                ws_f.data_ptr(), ws_f.numel(), None)
+        assert st == mate.MATE_OK          # nothing the host can see is wrong
+        st = mate.mate_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out_ref.data_ptr(), lse_ref.data_ptr(),
+                                do.data_ptr(), buf.data_ptr(), hk.ctypes.data, B, H, N, D, code, 0.125,
+                                *(g.data_ptr() for g in grads), ws_b.data_ptr(), ws_b.numel(), None)
+        assert st == mate.MATE_OK
+        torch.cuda.synchronize()
+        for t in (out, lse, *grads):
+            assert bool((t == 7).all())
+    with pytest.raises(mate.MateError) as e:      # the binding knows the shape its tables were built for
+        mate.attn_fwd(q, k, v, other, hk, 0.125)
+    assert e.value.status == mate.MATE_ERR_SHAPE
+
+
+def test_invalid_ids_are_reported_by_the_status_call():
+    from paper_2109_04312_amd import mate
+    w = small_workload(32, "bf16", B=3, N=150, H=2, max_rows=6, max_cols=4, max_global=5)
+    st = w.structure
+    table = np.flatnonzero(st.flags[1] == synth.TOK_LOCAL)
+    st.row_ids[1, table[3]] = -4                     # a negative id on a table token of sequence 1
+    r, c, f = hp.dev_structure(st)
+    seg = mate.build_segments(r, c, f)
+    assert mate.segments_status(seg) == mate.MATE_ERR_BAD_ID
+    # the tables are still consistent, so the attention runs and writes every row
+    q, k, v = (hp.to_dev(x, "bf16") for x in (w.q, w.k, w.v))
+    out, lse = mate.attn_fwd(q, k, v, seg, w.head_kind, 0.125, out=torch.full_like(q, float("nan")))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    st.row_ids[1, table[3]] = 0
+    st.flags[2, 5] = 9                               # a flag value above 2
+    r, c, f = hp.dev_structure(st)
+    assert mate.segments_status(mate.build_segments(r, c, f)) == mate.MATE_ERR_BAD_ID
 
 
 def test_step_replays_identically_from_a_captured_graph():

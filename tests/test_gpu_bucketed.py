@@ -66,7 +66,7 @@ def check(w, mode, pairs=None, label=""):
     hp.compare_segments(seg, w.structure, bucketed=mode)
     ref = hp.run_oracle(w, True, pairs, bucketed=mode)
     worst = hp.compare(got, ref, w, label or w.name)
-    print("   worst:", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in worst.items()}, flush=True)
+    print(hp.report(worst), flush=True)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -16,7 +16,7 @@ def check_dense(w, label=""):
     got, _ = hp.run_hip(w, backward=True, dense=True)
     ref = hp.run_oracle(w, True, None)
     worst = hp.compare(got, ref, w, label or w.name)
-    print("   worst:", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in worst.items()}, flush=True)
+    print(hp.report(worst), flush=True)
 
 
 @pytest.mark.parametrize("seed,N", [(0, 64), (1, 200), (2, 333), (3, 512), (4, 1024)])
@@ -61,8 +61,8 @@ def test_dense_config2_sampled_heads_and_agreement_with_segment_path():
     hp.compare(dense, ref, w, "cfg2 dense")
     seg, _ = hp.run_hip(w, backward=True, dense=False)
     for name in dense:
-        d = np.abs(dense[name] - seg[name]) / np.maximum(1.0, np.abs(seg[name]))
-        assert d.max() <= 2 * hp.TOL["bf16"]["max_abs"], (name, d.max())
+        d = np.abs(dense[name] - seg[name]) / hp.bound(name, seg[name], "bf16")
+        assert d.max() <= 2.0, (name, d.max())
 
 
 def test_dense_rejects_what_it_does_not_support():

@@ -21,14 +21,15 @@ def dev(x, dtype=torch.bfloat16):
 
 
 def close(got, want, what):
-    """bf16 output of an fp32-accumulated product: the tolerances of the bf16 attention path."""
+    """bf16 output of an fp32-accumulated product: |err| <= 2e-2 + 2^-8 |ref| (a bf16 store alone
+    costs |ref| 2^-9) and the bf16 path's mean-rel bound."""
     got = got.float().cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(got)), what
     err = np.abs(got - want)
-    rel = float((err / np.maximum(1.0, np.abs(want))).max())
+    ratio = float((err / hp.bound("projection", want, "bf16")).max()) if err.size else 0.0
     mean_rel = float(err.mean() / (np.abs(want).mean() + 1e-3))
-    print(f"   {what}: max-abs rel. to max(1,|ref|) {rel:.2e}, mean-rel {mean_rel:.2e}", flush=True)
-    assert rel <= hp.TOL["bf16"]["max_abs"] and mean_rel <= hp.TOL["bf16"]["mean_rel"], what
+    print(f"   {what}: max-abs {float(err.max()):.2e} = {ratio:.2f} x bound, mean-rel {mean_rel:.2e}", flush=True)
+    assert ratio <= 1.0 and mean_rel <= hp.TOL["bf16"]["mean_rel"], what
 
 
 def make(seed, B, N, H, E, pad_tail=0, scattered_pads=True, bias=True):
@@ -116,10 +117,11 @@ def test_layer_forward_end_to_end():
         yr = orc.project_out(orf, w_o, None, st.flags[sl])
         got = y[sl].float().cpu().numpy().astype(np.float64)
         err = np.abs(got - yr)
-        rel = float((err / np.maximum(1.0, np.abs(yr))).max())
+        ratio = float((err / hp.bound("projection", yr, "bf16")).max())
         mean_rel = float(err.mean() / (np.abs(yr).mean() + 1e-3))
-        print(f"   layer b={b}: max {rel:.2e} mean-rel {mean_rel:.2e}", flush=True)
-        assert rel <= 3e-2 and mean_rel <= 1.5e-2
+        print(f"   layer b={b}: max-abs {float(err.max()):.2e} = {ratio:.2f} x one step's bound, "
+              f"mean-rel {mean_rel:.2e}", flush=True)
+        assert ratio <= 1.5 and mean_rel <= 1.5e-2
 
 
 def test_unsupported_arguments():
