@@ -27,14 +27,75 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 D = 64
-# HBM bytes per launch on the headline workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0, the factors a plain copy of known size gives;
-# summaries under profiles/); a kernel or workload that is not listed reports null
-TRAFFIC = {"cfg4_B2_N8192_H16": {
-    "fwd_mfma_kernel": {"fetch_bytes": 62818 * 2048, "write_bytes": 41672 * 1024},
-    "bwd_dq_mfma_kernel": {"fetch_bytes": 91538 * 2048, "write_bytes": 41572 * 1024},
-    "bwd_dkv_mfma_kernel": {"fetch_bytes": 81600 * 2048, "write_bytes": 79383 * 1024},
-}}
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0   # what a plain copy of known size reads on these counters
+CSRC = os.path.join(ROOT, "paper_2109_04312_amd", "csrc")
+
+
+def sources_digest():
+    """sha256 over the kernel sources: a traffic figure measured on other sources is not
+    reported as if it belonged to this build."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def traffic_summary_path(workload):
+    return os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic_pmc.txt")
+
+
+def read_traffic(workload):
+    """HBM bytes per launch from the tracked rocprofv3 --pmc summary of this workload
+    (lines `counter <kernel> <FETCH_SIZE KiB> <WRITE_SIZE KiB>` and `sources <digest>`).
+    Returns ({kernel: {fetch_bytes, write_bytes}}, digest of the sources it was measured on)."""
+    path = traffic_summary_path(workload)
+    if not os.path.exists(path):
+        return {}, None
+    table, digest = {}, None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 2 and f[0] == "sources":
+            digest = f[1]
+        if len(f) == 4 and f[0] == "counter":
+            table[f[1]] = {"fetch_bytes": int(float(f[2]) * 1024 * FETCH_SCALE),
+                           "write_bytes": int(float(f[3]) * 1024 * WRITE_SCALE)}
+    return table, digest
+
+
+def summarize_pmc(fetch_dir, write_dir):
+    """Prints the machine-readable part of profiles/<workload>_hbm_traffic_pmc.txt from the csv
+    output of two `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --output-format csv` runs of this script."""
+    import csv
+    import glob
+
+    def per_kernel(d, counter):
+        acc = {}
+        for path in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(path)):
+                if row["Counter_Name"] == counter:
+                    name = row["Kernel_Name"].split("(")[0].replace("void mate::(anonymous namespace)::", "")
+                    acc.setdefault(name, {}).setdefault(row["Dispatch_Id"], 0.0)
+                    acc[name][row["Dispatch_Id"]] += float(row["Counter_Value"])
+        return {k: sum(v.values()) / len(v) for k, v in acc.items()}
+
+    fetch, write = per_kernel(fetch_dir, "FETCH_SIZE"), per_kernel(write_dir, "WRITE_SIZE")
+    print("sources", sources_digest())
+    for k in sorted(fetch):
+        if "mate" in k or "kernel" in k:
+            print("counter", k.replace(" ", ""), round(fetch[k]), round(write.get(k, 0.0)))
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def useful_pairs_per_view(st, bucketed=None):
@@ -63,14 +124,8 @@ def useful_pairs_per_view(st, bucketed=None):
     return out
 
 
-def cpu_baseline(w, pairs, total_heads, bucketed=None):
-    """Times the oracle (as it stands) on a few (b,h) pairs; scales to the whole batch."""
+def _oracle_fwd_bwd(w, pairs, bucketed=None):
     from oracle import mate_oracle as orc
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
     st = w.structure
     t0 = time.perf_counter()
     for b, h in pairs:
@@ -78,13 +133,35 @@ def cpu_baseline(w, pairs, total_heads, bucketed=None):
         args = (st.row_ids[b:b + 1], st.col_ids[b:b + 1], st.flags[b:b + 1], w.head_kind[h:h + 1], w.scale)
         orc.attn_forward(w.q[sl], w.k[sl], w.v[sl], *args, bucketed=bucketed)
         orc.attn_backward(w.q[sl], w.k[sl], w.v[sl], w.do[sl], *args, bucketed=bucketed)
-    dt = time.perf_counter() - t0
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(w, pairs, total_heads, bucketed=None):
+    """Times the oracle (as it stands) on a few (b,h) pairs; scales to the whole batch.  Also the
+    oracle on ONE thread on the short configuration 2 (one sequence, every head)."""
+    from paper_2109_04312_amd import synth
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threadpool_limits = None
+        cores = os.cpu_count() or 1
+    dt = _oracle_fwd_bwd(w, pairs, bucketed)
     B, H, N, _ = w.shape
     est = dt * total_heads / len(pairs)
-    return dict(value=B * N / est, unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=f"fwd+bwd of {len(pairs)} of {total_heads} (sequence, head) pairs "
-                       f"{pairs} of the same batch in {dt:.1f} s, scaled by {total_heads}/{len(pairs)}; "
-                       "segment tables not included")
+    res = dict(value=B * N / est, unit="tokens/s", cores=int(cores), kind="oracle", cpu_model=cpu_model(),
+               sample=f"fwd+bwd of {len(pairs)} of {total_heads} (sequence, head) pairs "
+                      f"{pairs} of the same batch in {dt:.1f} s, scaled by {total_heads}/{len(pairs)}; "
+                      "segment tables not included")
+    if threadpool_limits is not None:
+        w2 = synth.make_config(2)
+        B2, H2, N2, _ = w2.shape
+        with threadpool_limits(limits=1):
+            dt2 = _oracle_fwd_bwd(w2, [(0, h) for h in range(H2)])
+        res["one_thread_config2"] = dict(value=B2 * N2 / (dt2 * B2), unit="tokens/s", cores=1,
+                                         sample=f"{w2.name}: fwd+bwd of the {H2} heads of one of {B2} "
+                                                f"sequences on one thread in {dt2:.2f} s, scaled by {B2}")
+    return res
 
 
 def breakeven(steps, warmup):
@@ -213,9 +290,15 @@ def main():
     ap.add_argument("--breakeven", action="store_true",
                     help="only time the segment path (build + fwd + bwd) against the dense-mask "
                          "entry points (fwd + bwd) at short sequence lengths and exit")
+    ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"), default=None,
+                    help="print the machine-readable part of profiles/<workload>_hbm_traffic_pmc.txt from the "
+                         "csv output directories of two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE); no GPU needed")
     ap.add_argument("--projections", action="store_true",
                     help="time the QKV and output projection kernels on the configuration's layer shape and exit")
     args = ap.parse_args()
+    if args.summarize_pmc:
+        summarize_pmc(*args.summarize_pmc)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
@@ -268,13 +351,22 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    # the timed region: exactly `steps` steps between two synchronisations; an event every
+    # `block` steps on the stream the kernels run on gives the spread inside it
+    block = max(1, args.steps // 20)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps // block + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        if (i + 1) % block == 0:
+            marks[(i + 1) // block].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
+    block_ms = sorted(marks[i].elapsed_time(marks[i + 1]) / block for i in range(len(marks) - 1))
+    ms_median, ms_min = block_ms[len(block_ms) // 2], block_ms[0]
 
     # second pass of the same loop: HIP events recorded by the library around ONE kernel launch
     # per step (on the stream the kernels run on), cycling through the kernels
@@ -286,7 +378,7 @@ def main():
         return ev
     kernels = {"build_segments": mate.MATE_KERNEL_BUILD, "attn_fwd": mate.MATE_KERNEL_FWD,
                "attn_bwd_dq": mate.MATE_KERNEL_BWD_DQ, "attn_bwd_dkv": mate.MATE_KERNEL_BWD_DKV}
-    per_kernel = max(5, args.steps // len(kernels))
+    per_kernel = max(10, args.steps // len(kernels))
     pairs_ev = {name: [(new_event(), new_event()) for _ in range(per_kernel)] for name in kernels}
     t1 = time.perf_counter()
     for i in range(per_kernel):
@@ -296,21 +388,25 @@ def main():
             step()
     torch.cuda.synchronize()
     ms_per_step_pass2 = 1e3 * (time.perf_counter() - t1) / (per_kernel * len(kernels))
-    kernel_s = {}
+    kernel_s, kernel_median_s, kernel_min_s = {}, {}, {}
     for name in kernels:
-        tot = 0.0
+        samples = []
         for e0, e1 in pairs_ev[name]:
             ms = C.c_float()
             assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
-            tot += ms.value
-        kernel_s[name] = tot / per_kernel * 1e-3
+            samples.append(ms.value * 1e-3)
+        samples.sort()
+        kernel_s[name] = sum(samples) / len(samples)
+        kernel_median_s[name] = samples[len(samples) // 2]
+        kernel_min_s[name] = samples[0]
     t_build, t_fwd = kernel_s["build_segments"], kernel_s["attn_fwd"]
     t_dq, t_dkv = kernel_s["attn_bwd_dq"], kernel_s["attn_bwd_dkv"]
 
     pv = useful_pairs_per_view(st, bucketed)
     pairs = int(sum(pv[b, int(hk[h])] for b in range(B) for h in range(H)))
     tokens = B * N
-    nonpad = int((st.flags != synth.TOK_PAD).sum())
+    nonpad_b = (st.flags != synth.TOK_PAD).sum(axis=1)
+    nonpad = int(nonpad_b.sum())
     value = tokens / (elapsed / args.steps)
     # algorithmic flop per useful pair: forward 4*D (QK^T, PV); backward 10*D, of which the dQ
     # kernel is credited S, dP and dQ (6*D) and the dK/dV kernel dV and dK (4*D) -- its own
@@ -325,12 +421,98 @@ def main():
     alg_bytes = passes * 128 * nonpad * H
     hbm_gbs = alg_bytes / cand[dom][1] / 1e9
     t_attn = ms_per_step * 1e-3 - t_build
-    traffic = None if bucketed else TRAFFIC.get(w.name, {}).get(dom)   # measured in the default mode
+
+    # HBM traffic of the dominant kernel: from the tracked rocprofv3 --pmc summary of this
+    # workload, reported only if it was measured on the kernel sources this run was built from
+    table, digest = ({}, None) if bucketed else read_traffic(w.name)
+    fresh = digest is not None and digest == sources_digest()
     traffic_detail = None
-    if traffic is not None:
-        traffic_detail = dict(traffic, unit="HBM bytes per launch",
-                              source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy")
-        traffic = traffic["fetch_bytes"] + traffic["write_bytes"]
+    if dom in table:
+        traffic_detail = dict(table[dom], unit="HBM bytes per launch", profiled_on_sources=digest,
+                              matches_this_build=fresh,
+                              source=os.path.relpath(traffic_summary_path(w.name), ROOT)
+                                     + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy)")
+    traffic = table[dom]["fetch_bytes"] + table[dom]["write_bytes"] if (dom in table and fresh) else None
+
+    # ---- the box's own peaks, measured in this process -----------------------------------------
+    sink = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+    flop = C.c_double()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    mate.mate_probe_mfma(sink.data_ptr(), sink.numel() * 4, 2048, 100, C.byref(flop), mate._stream())  # warm-up
+    ev[0].record()
+    assert mate.mate_probe_mfma(sink.data_ptr(), sink.numel() * 4, 2048, 600, C.byref(flop), mate._stream()) == 0
+    ev[1].record()
+    src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev[2].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev[3].record()
+    torch.cuda.synchronize()
+    mfma_tflops = flop.value / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12
+    copy_gbs = 5 * 2 * src.numel() * 4 / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
+    del src, dst, sink
+    peaks_measured = {"mfma_bf16_tflops": mfma_tflops, "mfma_frac_of_nominal": mfma_tflops / PEAK_BF16_TFLOPS,
+                      "mfma_probe": "2048 workgroups x 4 wavefronts x 600 x 8 independent 32x32x16 bf16 MFMAs",
+                      "copy_gbs": copy_gbs, "copy_frac_of_nominal": copy_gbs / PEAK_HBM_GBS,
+                      "copy_probe": "256 MiB device-to-device copy x 5, read + write bytes"}
+
+    # ---- combined roofline: every (sequence, head) against the roof that binds it ----------------
+    # flop_h = 896 * useful pairs, bytes_h = 12 tensor passes * 128 B * non-pad tokens (+ 12 B of
+    # LSE / delta per token);  t_bound = sum_h max(flop_h / peak, bytes_h / bandwidth)
+    def t_bound(kinds, peak_tflops, bw_gbs):
+        t = 0.0
+        for b in range(B):
+            for h in range(H):
+                if int(hk[h]) in kinds:
+                    fl = 14 * D * int(pv[b, int(hk[h])])
+                    by = (12 * 128 + 12) * int(nonpad_b[b])
+                    t += max(fl / (peak_tflops * 1e12), by / (bw_gbs * 1e9))
+        return t
+
+    # ---- per head kind: the same tensors restricted to the row heads / the column heads ----------
+    per_kind = {}
+    if w.do is not None and not bucketed:
+        for kind, label in ((0, "row_heads"), (1, "col_heads")):
+            sel = [h for h in range(H) if int(hk[h]) == kind]
+            if not sel:
+                continue
+            qs, ks, vs, dos = (t[:, sel].contiguous() for t in (q, k, v, do))
+            Hs = len(sel)
+            hks = np.full(Hs, kind, np.uint8)
+            outs, lses = torch.empty_like(qs), torch.empty((B, Hs, N), dtype=torch.float32, device=dev)
+            g = [torch.empty_like(qs) for _ in range(3)]
+            wf = mate.workspace(B, Hs, N, D, code, False, dev)
+            wb = mate.workspace(B, Hs, N, D, code, True, dev)
+
+            def kind_step():
+                mate.attn_fwd(qs, ks, vs, seg, hks, w.scale, out=outs, lse=lses, ws=wf)
+                mate.attn_bwd(qs, ks, vs, outs, lses, dos, seg, hks, w.scale, dq=g[0], dk=g[1], dv=g[2], ws=wb)
+
+            n_k = max(10, args.steps // 4)
+            for _ in range(5):
+                kind_step()
+            torch.cuda.synchronize()
+            tk = time.perf_counter()
+            for _ in range(n_k):
+                kind_step()
+            torch.cuda.synchronize()
+            t_kind = (time.perf_counter() - tk) / n_k
+            tb = t_bound({kind}, PEAK_BF16_TFLOPS, PEAK_HBM_GBS)
+            kp = int(sum(pv[b, kind] for b in range(B)) * Hs)
+            per_kind[label] = {"heads": Hs, "ms_fwd_bwd": t_kind * 1e3, "useful_pairs": kp,
+                               "useful_tflops": 14 * D * kp / t_kind / 1e12,
+                               "t_bound_us": tb * 1e6, "frac_of_bound": tb / t_kind,
+                               "bound": "mfma" if 14 * D * kp / (PEAK_BF16_TFLOPS * 1e12) > (12 * 128 + 12) * nonpad * Hs / (PEAK_HBM_GBS * 1e9) else "hbm"}
+            del qs, ks, vs, dos, outs, lses, g, wf, wb
+
+    tb_nom = t_bound({0, 1}, PEAK_BF16_TFLOPS, PEAK_HBM_GBS)
+    tb_meas = t_bound({0, 1}, mfma_tflops, copy_gbs)
+    combined = {"t_bound_us": tb_nom * 1e6, "frac_of_attn_time": tb_nom / t_attn,
+                "t_bound_us_measured_peaks": tb_meas * 1e6, "frac_of_attn_time_measured_peaks": tb_meas / t_attn,
+                "definition": "sum over (sequence, head) of max(896 * useful pairs / MFMA peak, "
+                              "1548 B * non-pad tokens / HBM bandwidth), over the time of forward + backward"}
 
     res = {
         "metric": "MATE attn fwd+bwd tokens/s & useful-pair TFLOP/s, seq 8192, 16 heads, 1 GPU",
@@ -341,18 +523,30 @@ def main():
                    "col_heads": int((hk == 1).sum()), "non_pad_tokens": nonpad, "useful_pairs": pairs,
                    "step": ("mate_build_segments_bucketed" if bucketed else "mate_build_segments")
                            + " + mate_attn_fwd + mate_attn_bwd"},
+        "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+        "ms_per_step_spread": f"median and min over blocks of {block} consecutive steps of the timed region (HIP events)",
+        "non_pad_tokens_per_s": nonpad / (elapsed / args.steps),
         "useful_tflops": 14 * D * pairs / (elapsed / args.steps) / 1e12,
         "useful_tflops_attn_only": 14 * D * pairs / t_attn / 1e12,
         "tokens_per_s_attn_only": tokens / t_attn,
         "kernel_ms": {k: v * 1e3 for k, v in kernel_s.items()},
+        "kernel_ms_median": {k: v * 1e3 for k, v in kernel_median_s.items()},
+        "kernel_ms_min": {k: v * 1e3 for k, v in kernel_min_s.items()},
         "ms_per_step_event_pass": ms_per_step_pass2,
         "flop_convention": "fwd 4*D, bwd 10*D flop per useful (query,key) pair; exp not counted",
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_detail": traffic_detail,
+                     "frac_of_measured_peak": ach / mfma_tflops,
+                     "limiter": "the kernel is a dense contraction, so it is priced against the matrix peak; what "
+                                "limits it today is SIMD issue time (vector ALU + matrix instructions taking turns) "
+                                "and per-unit latency, see profiles/" + w.name + "_sq_counters_pmc.txt",
                      "algorithmic_flop_per_launch": cand[dom][0],
-                     "avg_launch_us": cand[dom][1] * 1e6,
+                     "avg_launch_us": cand[dom][1] * 1e6, "median_launch_us": kernel_median_s[{"fwd_mfma_kernel": "attn_fwd", "bwd_dq_mfma_kernel": "attn_bwd_dq", "bwd_dkv_mfma_kernel": "attn_bwd_dkv"}[dom]] * 1e6,
                      "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved": hbm_gbs,
                                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS}},
+        "combined_roofline": combined,
+        "per_kind": per_kind,
+        "peaks_measured": peaks_measured,
         "segment_builder": {"us": t_build * 1e6, "keys_per_s": 2 * tokens / t_build,
                             "algorithmic_GBps": 30.0 * tokens / t_build / 1e9,
                             "frac_hbm": 30.0 * tokens / t_build / 1e9 / PEAK_HBM_GBS},
@@ -364,7 +558,6 @@ def main():
         sample = [(b, h) for b in range(min(B, 2)) for h in rows_h + cols_h]
         res["cpu_baseline"] = cpu_baseline(w, sample, B * H, bucketed)
     print(json.dumps(res))
-
 
 if __name__ == "__main__":
     main()

@@ -154,6 +154,15 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
                                  int32_t* counts, void* stream);
 
 /*
+ * Status of a table buffer (waits for `stream`; copies a few words per sequence to the host,
+ * allocates nothing): MATE_OK, MATE_ERR_SHAPE if the buffer does not hold tables built for this
+ * (B, N) -- never built, or built for another shape -- or MATE_ERR_BAD_ID if the builder met a
+ * negative id on a LOCAL token or a flag above 2.  This is the call that reports what the
+ * asynchronous builder and attention calls cannot return themselves.
+ */
+mate_status mate_segments_status(const void* segments, int B, int N, void* stream);
+
+/*
  * Copies the attention windows of one view to a HOST array (test and inspection hook; waits
  * for `stream`): window[b][s] = {lo, hi}, the sorted slots [lo, hi) whose tokens slot s attends
  * to besides the global part -- its segment, in bucketed mode cut to buckets j - 1 .. j + 1 of
@@ -179,7 +188,15 @@ mate_status mate_segments_export_windows(const void* segments, int B, int N, int
  *   out         [B, H, N, D] dtype t;  lse [B, H, N] float
  *   workspace   mate_workspace_bytes(..., 0) bytes (may be NULL if that is 0)
  *
- * Asynchronous on `stream`.  Does not read the builder's status word.
+ * Asynchronous on `stream`, so what only the device can see is not in the return value:
+ *   - `segments` must point to mate_segments_bytes(B, N) bytes.  If they do not hold tables
+ *     built for this (B, N) (never built, or built for another shape) every workgroup leaves
+ *     before using them: `out`, `lse` (and dq, dk, dv in the backward) are left exactly as
+ *     they were.  mate_segments_status reports MATE_ERR_SHAPE for such a buffer.
+ *   - Tables built from invalid ids or flags (MATE_ERR_BAD_ID from mate_segments_status) are
+ *     still consistent tables -- the builder orders a negative id as an unsigned number and
+ *     treats a flag above 2 as padding -- so the attention runs on them and its results are
+ *     those of that reading of the input.
  */
 mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const void* segments,
                           const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
@@ -217,6 +234,11 @@ mate_status mate_attn_bwd(const void* q, const void* k, const void* v, const voi
  * Everything else as above.  Asynchronous on `stream`; deterministic.
  */
 size_t mate_dense_workspace_bytes(int B, int H, int N);
+/* The choice Section 3.1 describes ("the best of the two functionally equivalent
+ * implementations"): non-zero if the dense-mask variant is the faster one for this shape and
+ * dtype on MI355X (measured break-even: bf16, N <= MATE_DENSE_PREFERRED_MAX_N), zero if the
+ * segment path is (always for MATE_F32, which the dense variant does not support). */
+int mate_attn_prefers_dense(int B, int H, int N, mate_dtype t);
 mate_status mate_attn_fwd_dense(const void* q, const void* k, const void* v,
                                 const int32_t* row_ids, const int32_t* col_ids,
                                 const uint8_t* flags, const uint8_t* head_kind, int B, int H,
@@ -269,6 +291,17 @@ enum { MATE_KERNEL_NONE = 0, MATE_KERNEL_BUILD = 1, MATE_KERNEL_FWD = 2, MATE_KE
        MATE_KERNEL_BWD_DKV = 4, MATE_KERNEL_FWD_DENSE = 5, MATE_KERNEL_BWD_DQ_DENSE = 6,
        MATE_KERNEL_BWD_DKV_DENSE = 7, MATE_KERNEL_QKV_PROJECT = 8, MATE_KERNEL_OUT_PROJECT = 9 };
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event);
+
+/*
+ * Measurement aid, not part of the computation: launches a kernel that only issues independent
+ * 32x32x16 bf16 matrix instructions (`workgroups` x 4 wavefronts x `iters` x 8 of them), so a
+ * benchmark can time what the matrix cores of this machine sustain, beside the nominal peak.
+ *   sink        workgroups * 256 floats, overwritten (keeps the work alive)
+ *   flop        HOST, may be NULL: receives the number of floating-point operations launched
+ * Asynchronous on `stream`.
+ */
+mate_status mate_probe_mfma(float* sink, size_t sink_bytes, int workgroups, int iters,
+                            double* flop, void* stream);
 
 /* Static, NUL-terminated description of a status code (HOST pointer, never NULL). */
 const char* mate_status_string(mate_status s);

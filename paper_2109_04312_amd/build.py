@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmate.so")
-SOURCES = ["api.hip", "segments.hip", "positions.hip", "proj_mfma.hip", "attn_scalar.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "attn_dense_mfma.hip"]
+SOURCES = ["api.hip", "segments.hip", "positions.hip", "probe.hip", "proj_mfma.hip", "attn_scalar.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "attn_dense_mfma.hip"]
 # packed-fp32 instructions are switched off on purpose (device code only).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature",
          "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]

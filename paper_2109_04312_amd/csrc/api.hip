@@ -2,9 +2,8 @@
 // stream.  No allocation, no global state.
 #include <hip/hip_runtime.h>
 
-#include <cstring>
 #include <algorithm>
-#include <vector>
+#include <cstring>
 
 #include "../../include/mate.h"
 #include "launch.h"
@@ -130,35 +129,78 @@ mate_status mate_segments_export(const void* segments, int B, int N, int view, i
   const SegLayout lay(B, N);
   const int* w = static_cast<const int*>(segments);
   const int* vb = w + lay.view0 + (size_t)view * lay.view_stride;
-  std::vector<int> head(kHdrWords + (size_t)B * kCountWords);
+  int head[kHdrWords];
 #define MATE_D2H(dst, src, words)                                                             \
   if (hipMemcpyAsync(dst, src, (size_t)(words) * sizeof(int), hipMemcpyDeviceToHost, s) !=    \
       hipSuccess)                                                                             \
     return MATE_ERR_HIP;
-  MATE_D2H(head.data(), w, head.size());
+  MATE_D2H(head, w, kHdrWords);
   if (perm) MATE_D2H(perm, vb + lay.perm, (size_t)B * N);
   if (seg_off) MATE_D2H(seg_off, vb + lay.seg_off, (size_t)B * (N + 1));
   if (seg_of_tok) MATE_D2H(seg_of_tok, vb + lay.seg_of_tok, (size_t)B * N);
   if (global_idx) MATE_D2H(global_idx, w + lay.global_idx, (size_t)B * N);
-#undef MATE_D2H
   if (hipStreamSynchronize(s) != hipSuccess) return MATE_ERR_HIP;
   if (head[0] != kMagic || head[1] != B || head[2] != N) return MATE_ERR_SHAPE;
+  // per-sequence counts, a few sequences per copy through a fixed buffer (no allocation)
+  constexpr int kBatch = 64;
+  int cnt[kBatch * kCountWords];
   int bad = 0;
-  for (int b = 0; b < B; ++b) {
-    const int* c = head.data() + kHdrWords + (size_t)b * kCountWords;
-    // the builder writes the valid part of each list only: the rest is -1 by this function's contract
-    if (perm) std::fill(perm + (size_t)b * N + c[C_L], perm + (size_t)(b + 1) * N, -1);
-    if (global_idx) std::fill(global_idx + (size_t)b * N + c[C_G], global_idx + (size_t)(b + 1) * N, -1);
-    if (seg_off)
-      std::fill(seg_off + (size_t)b * (N + 1) + c[C_SROW + view] + 1, seg_off + (size_t)(b + 1) * (N + 1), -1);
-    if (counts) {
-      counts[3 * b + 0] = c[C_G];
-      counts[3 * b + 1] = c[C_L];
-      counts[3 * b + 2] = c[C_SROW + view];
+  for (int b0 = 0; b0 < B; b0 += kBatch) {
+    const int nb = std::min(kBatch, B - b0);
+    MATE_D2H(cnt, w + lay.counts + (size_t)b0 * kCountWords, (size_t)nb * kCountWords);
+    if (hipStreamSynchronize(s) != hipSuccess) return MATE_ERR_HIP;
+    for (int b = b0; b < b0 + nb; ++b) {
+      const int* c = cnt + (size_t)(b - b0) * kCountWords;
+      // the builder writes the valid part of each list only: the rest is -1 by this function's contract
+      if (perm) std::fill(perm + (size_t)b * N + c[C_L], perm + (size_t)(b + 1) * N, -1);
+      if (global_idx) std::fill(global_idx + (size_t)b * N + c[C_G], global_idx + (size_t)(b + 1) * N, -1);
+      if (seg_off)
+        std::fill(seg_off + (size_t)b * (N + 1) + c[C_SROW + view] + 1, seg_off + (size_t)(b + 1) * (N + 1), -1);
+      if (counts) {
+        counts[3 * b + 0] = c[C_G];
+        counts[3 * b + 1] = c[C_L];
+        counts[3 * b + 2] = c[C_SROW + view];
+      }
+      bad |= c[5] | c[6];  // per-view "bad id or flag seen" words
     }
-    bad |= c[5] | c[6];  // per-view "bad id or flag seen" words
+  }
+#undef MATE_D2H
+  return bad ? MATE_ERR_BAD_ID : MATE_OK;
+}
+
+mate_status mate_segments_status(const void* segments, int B, int N, void* stream) {
+  if (!segments) return MATE_ERR_NULL;
+  if (!shape_ok(B, N)) return MATE_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int* w = static_cast<const int*>(segments);
+  int head[kHdrWords];
+  if (hipMemcpyAsync(head, w, sizeof(head), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return MATE_ERR_HIP;
+  if (head[0] != kMagic || head[1] != B || head[2] != N) return MATE_ERR_SHAPE;
+  // the per-sequence words, a few sequences per copy through a fixed buffer (no allocation)
+  constexpr int kBatch = 64;
+  int cnt[kBatch * kCountWords];
+  int bad = 0;
+  for (int b0 = 0; b0 < B; b0 += kBatch) {
+    const int n = std::min(kBatch, B - b0);
+    if (hipMemcpyAsync(cnt, w + SegLayout(B, N).counts + (size_t)b0 * kCountWords,
+                       (size_t)n * kCountWords * sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      return MATE_ERR_HIP;
+    for (int b = 0; b < n; ++b) bad |= cnt[b * kCountWords + 5] | cnt[b * kCountWords + 6];
   }
   return bad ? MATE_ERR_BAD_ID : MATE_OK;
+}
+
+int mate_attn_prefers_dense(int B, int H, int N, mate_dtype t) {
+  (void)B;
+  (void)H;
+  // Measured on MI355X with tables shaped like the short benchmark configuration (B = 32,
+  // H = 12): build + forward + backward of the segment path against forward + backward of the
+  // dense-mask variant.  Dense wins up to N = 256 and loses from N = 384 on; the batch and head
+  // counts scale both sides alike, so they do not enter.
+  return t == MATE_BF16 && N >= 1 && N <= MATE_DENSE_PREFERRED_MAX_N;
 }
 
 namespace {
@@ -302,6 +344,16 @@ mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event)
   g_profile_hook.start = static_cast<hipEvent_t>(start_event);
   g_profile_hook.stop = static_cast<hipEvent_t>(stop_event);
   return MATE_OK;
+}
+
+mate_status mate_probe_mfma(float* sink, size_t sink_bytes, int workgroups, int iters,
+                            double* flop, void* stream) {
+  if (!sink) return MATE_ERR_NULL;
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24)) return MATE_ERR_SHAPE;
+  if (sink_bytes < (size_t)workgroups * 256 * sizeof(float)) return MATE_ERR_WORKSPACE;
+  if (flop) *flop = mfma_probe_flop(workgroups, iters);
+  return launch_mfma_probe(sink, workgroups, iters, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MATE_OK : MATE_ERR_HIP;
 }
 
 const char* mate_status_string(mate_status s) {

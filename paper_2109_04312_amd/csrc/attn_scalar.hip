@@ -75,6 +75,11 @@ __device__ inline Item make_item(const SegTables& t, int b, int N, int view, int
   return it;
 }
 
+// Tables built for another (B, N), or never built: every wavefront leaves before reading them.
+__device__ inline bool tables_ok(const AttnArgs& a) {
+  return a.seg.hdr[0] == kMagic && a.seg.hdr[1] == a.B && a.seg.hdr[2] == a.N;
+}
+
 template <typename T>
 __device__ inline float dot_row(const float* __restrict__ a, const T* __restrict__ row) {
   float acc = 0.f;
@@ -87,7 +92,7 @@ template <typename T>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void fwd_scalar_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y, x = blockIdx.x * kWavesPerBlock + wave;
-  if (x >= a.N) return;
+  if (x >= a.N || !tables_ok(a)) return;
   const Item it = make_item(a.seg, b, a.N, a.head_kind[h], x);
   const size_t bh = ((size_t)b * a.H + h) * a.N;
   const T* Q = static_cast<const T*>(a.q) + bh * D;
@@ -133,7 +138,7 @@ template <typename T>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void bwd_dq_scalar_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y, x = blockIdx.x * kWavesPerBlock + wave;
-  if (x >= a.N) return;
+  if (x >= a.N || !tables_ok(a)) return;
   const Item it = make_item(a.seg, b, a.N, a.head_kind[h], x);
   const size_t bh = ((size_t)b * a.H + h) * a.N;
   const T* Q = static_cast<const T*>(a.q) + bh * D;
@@ -187,7 +192,7 @@ template <typename T>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void bwd_dkv_scalar_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y, x = blockIdx.x * kWavesPerBlock + wave;
-  if (x >= a.N) return;
+  if (x >= a.N || !tables_ok(a)) return;
   const Item it = make_item(a.seg, b, a.N, a.head_kind[h], x);
   const size_t bh = ((size_t)b * a.H + h) * a.N;
   const T* Q = static_cast<const T*>(a.q) + bh * D;

@@ -82,6 +82,11 @@ hipError_t launch_out_project(const void* o, const void* w_o, const float* bias,
                               const unsigned char* flags, int B, int N, int H, int E, void* y,
                               hipStream_t stream);
 
+// Measurement aid: `workgroups` x 4 wavefronts each issue `iters` x 8 independent 32x32x16 bf16
+// MFMAs and write one float per thread to `sink` (workgroups * 256 floats).
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t stream);
+double mfma_probe_flop(int workgroups, int iters);
+
 // Scalar (non-MFMA) kernels: fp32 arithmetic throughout, one wavefront per query / key.
 // They serve dtype f32 and are the fallback-free reference-quality path for it.
 hipError_t launch_fwd_scalar(const AttnArgs& a, bool bf16, hipStream_t stream);

@@ -122,10 +122,16 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   w.bh = b * a.H + h;
   const int4* rec = glob ? a.seg.gunit + ((size_t)b * T + k) * 2
                          : a.seg.unit[w.view] + ((size_t)b * (T + 2) + k) * 2;
+  // The header is fetched together with the record (one scalar round trip for both): tables
+  // built for another (B, N), or never built, make every workgroup leave before it uses a word
+  // of them.  All of these reads stay inside the mate_segments_bytes(B, N) bytes the caller
+  // must provide.
+  const int h_magic = a.seg.hdr[0], h_B = a.seg.hdr[1], h_N = a.seg.hdr[2];
   const int4 r0 = rec[0], r1 = rec[1];
   const int* cnt = a.seg.counts + (size_t)b * kCountWords;
   UnitPlan& u = w.u;
   u.kind = r0.x;
+  if (h_magic != kMagic || h_B != a.B || h_N != a.N) return false;
   if (u.kind == UNIT_NONE) return false;
   u.t0 = r0.y;
   u.s_lo = r0.z;

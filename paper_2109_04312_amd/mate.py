@@ -27,8 +27,8 @@ MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
            "mate_build_segments_bucketed", "mate_cell_positions", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
-           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
-           "mate_status_string"]
+           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_attn_prefers_dense", "mate_segments_status", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
+           "mate_probe_mfma", "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
 MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
 MATE_KERNEL_FWD_DENSE, MATE_KERNEL_BWD_DQ_DENSE, MATE_KERNEL_BWD_DKV_DENSE = 5, 6, 7
@@ -63,6 +63,10 @@ _lib.mate_attn_bwd.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _
                                _p, _p, _p, _p, _sz, _p]
 _lib.mate_dense_workspace_bytes.restype = _sz
 _lib.mate_dense_workspace_bytes.argtypes = [_i, _i, _i]
+_lib.mate_attn_prefers_dense.restype = _i
+_lib.mate_attn_prefers_dense.argtypes = [_i, _i, _i, _i]
+_lib.mate_segments_status.restype = _i
+_lib.mate_segments_status.argtypes = [_p, _i, _i, _p]
 _lib.mate_attn_fwd_dense.restype = _i
 _lib.mate_attn_fwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _p, _p]
 _lib.mate_attn_bwd_dense.restype = _i
@@ -74,6 +78,8 @@ _lib.mate_out_project.restype = _i
 _lib.mate_out_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p]
 _lib.mate_profile_kernel.restype = _i
 _lib.mate_profile_kernel.argtypes = [_i, _p, _p]
+_lib.mate_probe_mfma.restype = _i
+_lib.mate_probe_mfma.argtypes = [_p, _sz, _i, _i, C.POINTER(C.c_double), _p]
 _lib.mate_status_string.restype = C.c_char_p
 _lib.mate_status_string.argtypes = [_i]
 
@@ -87,7 +93,10 @@ mate_segments_export_windows = _lib.mate_segments_export_windows
 mate_attn_fwd = _lib.mate_attn_fwd
 mate_attn_bwd = _lib.mate_attn_bwd
 mate_profile_kernel = _lib.mate_profile_kernel
+mate_probe_mfma = _lib.mate_probe_mfma
 mate_dense_workspace_bytes = _lib.mate_dense_workspace_bytes
+mate_attn_prefers_dense = _lib.mate_attn_prefers_dense
+mate_segments_status = _lib.mate_segments_status
 mate_attn_fwd_dense = _lib.mate_attn_fwd_dense
 mate_attn_bwd_dense = _lib.mate_attn_bwd_dense
 mate_qkv_project = _lib.mate_qkv_project
@@ -200,8 +209,14 @@ def workspace(B, H, N, D, dtype_code, for_bwd, device) -> torch.Tensor:
     return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 
+def _check_tables(seg: Segments, B: int, N: int):
+    if (seg.B, seg.N) != (B, N) or seg.buf.numel() < mate_segments_bytes(B, N):
+        raise MateError(MATE_ERR_SHAPE, f"segment tables are for (B, N) = ({seg.B}, {seg.N}), tensors for ({B}, {N})")
+
+
 def attn_fwd(q, k, v, seg: Segments, head_kind, scale: float, out=None, lse=None, ws=None):
     B, H, N, D = q.shape
+    _check_tables(seg, B, N)
     hk = _head_kind_host(head_kind, H)
     code = _dtype_code(q)
     if out is None:
@@ -220,6 +235,7 @@ def attn_fwd(q, k, v, seg: Segments, head_kind, scale: float, out=None, lse=None
 def attn_bwd(q, k, v, out, lse, dout, seg: Segments, head_kind, scale: float,
              dq=None, dk=None, dv=None, ws=None):
     B, H, N, D = q.shape
+    _check_tables(seg, B, N)
     hk = _head_kind_host(head_kind, H)
     code = _dtype_code(q)
     dq = torch.empty_like(q) if dq is None else dq
@@ -301,7 +317,13 @@ def out_project(o, w_o, bias, flags, y=None):
     return y
 
 
-def prefer_dense(N: int, dtype: torch.dtype = torch.bfloat16) -> bool:
-    """Which of the two equivalent implementations to call for sequence length N (the measured
-    break-even on MI355X; `python bench.py --breakeven` re-measures it)."""
-    return dtype == torch.bfloat16 and N <= MATE_DENSE_PREFERRED_MAX_N
+def prefer_dense(B: int, H: int, N: int, dtype: torch.dtype = torch.bfloat16) -> bool:
+    """Which of the two equivalent implementations to call (the library's own choice,
+    mate_attn_prefers_dense: the measured break-even on MI355X)."""
+    code = MATE_BF16 if dtype == torch.bfloat16 else MATE_F32
+    return bool(mate_attn_prefers_dense(int(B), int(H), int(N), code))
+
+
+def segments_status(seg: Segments) -> int:
+    """MATE_OK, MATE_ERR_SHAPE or MATE_ERR_BAD_ID for a table buffer (synchronises)."""
+    return int(mate_segments_status(seg.buf.data_ptr(), seg.B, seg.N, _stream()))

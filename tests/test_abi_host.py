@@ -105,6 +105,25 @@ def test_argument_errors_of_the_later_entry_points(mate):
         assert op(*args) == want, (pos, val)
 
 
+def test_choice_between_the_two_implementations(mate):
+    """Section 3.1: the faster of the two equivalent implementations is used per case.  The
+    library's choice is the measured break-even: bf16 up to MATE_DENSE_PREFERRED_MAX_N."""
+    f = mate.mate_attn_prefers_dense
+    edge = mate.MATE_DENSE_PREFERRED_MAX_N
+    assert f(32, 12, 128, mate.MATE_BF16) == 1 and f(1, 1, edge, mate.MATE_BF16) == 1
+    assert f(32, 12, edge + 1, mate.MATE_BF16) == 0 and f(2, 16, 8192, mate.MATE_BF16) == 0
+    assert f(1, 4, 128, mate.MATE_F32) == 0          # the dense variant is bf16 only
+    assert f(1, 4, 0, mate.MATE_BF16) == 0
+    assert edge <= mate.MATE_DENSE_MAX_N
+
+
+def test_status_call_argument_errors(mate):
+    fake = 0x1000  # never dereferenced
+    assert mate.mate_segments_status(None, 1, 128, None) == mate.MATE_ERR_NULL
+    assert mate.mate_segments_status(fake, 0, 128, None) == mate.MATE_ERR_SHAPE
+    assert mate.mate_segments_status(fake, 1, mate.MATE_MAX_N + 1, None) == mate.MATE_ERR_SHAPE
+
+
 def test_bench_pair_count_matches_the_oracle():
     """bench.py counts useful (query, key) pairs with its own vectorised formula (it may not use
     the oracle outside its cpu_baseline leg); here that bookkeeping is held against the oracle's
