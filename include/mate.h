@@ -252,6 +252,29 @@ mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, con
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * mate_attn_bwd_dense for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments without the workspace, same kernels, same results bit for bit.  The scratch
+ * (two floats per (b, h, position)) lives in a static device array of MATE_STATIC_SCRATCH_BYTES
+ * inside the library, one copy per GPU, held until the process ends; its address is looked up
+ * on the first call on each device.  The call allocates and frees nothing.
+ *
+ *   mate_dense_workspace_bytes(B, H, N) > MATE_STATIC_SCRATCH_BYTES  ->  MATE_ERR_WORKSPACE
+ *   (the limit is B * H * N <= 524288, e.g. 32 x 16 x 1024); nothing is launched then.
+ *
+ * Every call on a GPU uses that GPU's one array: two calls that overlap on the same GPU (on
+ * different streams, or from different threads) race on it and must be serialised by the
+ * caller.  Calls that follow each other on one stream are safe, whatever their sizes.
+ */
+enum { MATE_STATIC_SCRATCH_BYTES = 4 * 1024 * 1024 };
+mate_status mate_attn_bwd_dense_static(const void* q, const void* k, const void* v, const void* out,
+                                       const float* lse, const void* dout, const int32_t* row_ids,
+                                       const int32_t* col_ids, const uint8_t* flags,
+                                       const uint8_t* head_kind, int B, int H, int N, int D,
+                                       mate_dtype t, float scale, void* dq, void* dk, void* dv,
+                                       void* stream);
+
+/*
  * The projections either side of the attention, bf16 on the matrix cores.
  *
  * mate_qkv_project: q[b,i,k,:] = W_Q^i x[b,k,:] (+ bias), likewise K and V -- the products

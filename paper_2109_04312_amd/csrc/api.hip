@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 
 #include "../../include/mate.h"
@@ -11,6 +12,11 @@
 #include "stream_plan.h"
 
 using namespace mate;
+
+// Scratch of mate_attn_bwd_dense_static: one copy per GPU, held until the process ends.  In host
+// code this name is only a stand-in; the device address comes from hipGetSymbolAddress (below),
+// once per device, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[MATE_STATIC_SCRATCH_BYTES];
 
 namespace mate {
 // Measurement hook (see mate_profile_kernel): events to record around the next launch of one
@@ -334,6 +340,49 @@ mate_status mate_attn_bwd_dense(const void* q, const void* k, const void* v, con
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.delta = static_cast<float*>(workspace);
   a.nlse = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(B, H, N));
+  return launch_bwd_dense(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, or null
+
+// Address of the current device's copy of `scratch`; looked up on the first call on that device.
+mate_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MATE_ERR_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MATE_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing threads store the same value
+  }
+  *out = p;
+  return MATE_OK;
+}
+}  // namespace
+
+mate_status mate_attn_bwd_dense_static(const void* q, const void* k, const void* v, const void* out,
+                                       const float* lse, const void* dout, const int32_t* row_ids,
+                                       const int32_t* col_ids, const uint8_t* flags,
+                                       const uint8_t* head_kind, int B, int H, int N, int D,
+                                       mate_dtype t, float scale, void* dq, void* dk, void* dv,
+                                       void* stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return MATE_ERR_NULL;
+  DenseArgs a;
+  mate_status st = fill_dense(a, row_ids, col_ids, flags, head_kind, B, H, N, D, t, scale);
+  if (st != MATE_OK) return st;
+  if (mate_dense_workspace_bytes(B, H, N) > (size_t)MATE_STATIC_SCRATCH_BYTES) return MATE_ERR_WORKSPACE;
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != MATE_OK) return st;
+  a.q = q; a.k = k; a.v = v; a.o = out; a.dout = dout;
+  a.lse = const_cast<float*>(lse);
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  // Nothing has to be cleared: the dQ kernel writes both arrays at every position before the
+  // dK/dV kernel reads them, for this call's (B, H, N); what an earlier call left behind lies
+  // beyond that or is overwritten.
+  a.delta = static_cast<float*>(ws);
+  a.nlse = reinterpret_cast<float*>(static_cast<char*>(ws) + delta_bytes(B, H, N));
   return launch_bwd_dense(a, static_cast<hipStream_t>(stream)) == hipSuccess ? MATE_OK : MATE_ERR_HIP;
 }
 

@@ -27,7 +27,7 @@ MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
            "mate_build_segments_bucketed", "mate_cell_positions", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
-           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_attn_prefers_dense", "mate_segments_status", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
+           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_attn_bwd_dense_static", "mate_attn_prefers_dense", "mate_segments_status", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
            "mate_probe_mfma", "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
 MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
@@ -72,6 +72,9 @@ _lib.mate_attn_fwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i,
 _lib.mate_attn_bwd_dense.restype = _i
 _lib.mate_attn_bwd_dense.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
                                      _p, _p, _p, _p, _sz, _p]
+_lib.mate_attn_bwd_dense_static.restype = _i
+_lib.mate_attn_bwd_dense_static.argtypes = [_p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f,
+                                            _p, _p, _p, _p]
 _lib.mate_qkv_project.restype = _i
 _lib.mate_qkv_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p, _p, _p]
 _lib.mate_out_project.restype = _i
@@ -99,6 +102,8 @@ mate_attn_prefers_dense = _lib.mate_attn_prefers_dense
 mate_segments_status = _lib.mate_segments_status
 mate_attn_fwd_dense = _lib.mate_attn_fwd_dense
 mate_attn_bwd_dense = _lib.mate_attn_bwd_dense
+mate_attn_bwd_dense_static = _lib.mate_attn_bwd_dense_static
+MATE_STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
 mate_qkv_project = _lib.mate_qkv_project
 mate_out_project = _lib.mate_out_project
 
