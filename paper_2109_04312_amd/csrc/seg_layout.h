@@ -13,16 +13,21 @@
 //     seg_of_tok[B][N]   token position -> segment index, -1 for GLOBAL / PAD
 //     slot_rng[B][N][2]  per sorted slot: [first slot, one-past-last slot) of its window = its
 //                        segment, in bucketed mode cut to its own and the two adjacent buckets
-//     unit[B][T + 2][8]  work units of table-token owners (one per 128-slot tile of the sorted
-//                        order), then of pad owners (1024 pad positions each), then empty
-//                        records
+//     unit[B][U][8]      work units of table-token owners (up to 128 consecutive slots of the
+//                        sorted order each), longest streamed side first, then of pad owners
+//                        (1024 pad positions each), then empty records; U = view_units(N)
 //
 // A work unit is what one workgroup of the bf16 attention kernels does: it owns up to 128 rows
 // and streams 64-row tiles of the other side.  Record (8 words):
 //   kind (0 none, 1 question-token owner, 2 table-token owner, 3 pad owner), first owned slot,
 //   streamed sorted-slot window [lo, hi), first and one-past-last streamed tile, partial-result
-//   slot or -1, 0
-// For a table-token owner [lo, hi) is the union of the windows of its 128 slots.
+//   slot or -1, one past the last owned slot (table-token owners)
+// For a table-token owner [lo, hi) is the union of the windows of its slots.  Its slots are a
+// 128-slot piece of a "run": a segment of at least kBigSegment slots is a run of its own, the
+// shorter segments between two such segments form one run.  So no unit straddles the boundary
+// of a long segment (it would stream both segments' windows with half of its wavefronts idle
+// on each, and be the longest unit of the launch).  If that needs more records than there
+// are, the sorted order is cut every 128 slots regardless of segments.
 // The streamed side of question-token owners is the whole sequence; it is cut into chunks of at
 // least kMinChunkTiles tiles, one unit each, that leave partial results.
 #pragma once
@@ -39,12 +44,15 @@ constexpr int kTileSlots = 128;    // sorted slots per tile (= rows owned by one
 constexpr int kMaxTiles = 128;     // MATE_MAX_N / kTileSlots
 constexpr int kPadSlots = 1024;    // pad positions zero-filled by one pad unit
 constexpr int kUnitWords = 8;
+constexpr int kBigSegment = 128;   // a segment this long starts a unit of its own
 constexpr int BM = kTileSlots;     // owned rows per workgroup (32 per wavefront)
 constexpr int BN = 64;             // streamed rows per tile
 constexpr int kMinChunkTiles = 16; // streamed tiles per chunk of a question-token owner
 enum { UNIT_NONE = 0, UNIT_GLOBAL = 1, UNIT_LOCAL = 2, UNIT_PAD = 3 };
 
 __host__ __device__ inline int owner_slots(int N) { return (N + BM - 1) / BM; }  // T
+// Unit records per (sequence, view): table-token owners, pad owners, spare.
+__host__ __device__ inline int view_units(int N) { const int T = owner_slots(N); return T + T / 2 + 2; }
 
 // How the streamed side of question-token owners is chunked.  n_gt * n_chunks <= T.
 struct GlobalSplit {
@@ -69,7 +77,7 @@ __host__ __device__ inline size_t align4(size_t w) { return (w + 3) & ~size_t(3)
 
 struct SegLayout {
   int B, N;
-  int tiles;
+  int tiles, units;
   size_t counts, global_idx, pad_idx, gunit, view0, view_stride, perm, seg_off, seg_of_tok,
       slot_rng, unit, total;
 
@@ -79,6 +87,7 @@ struct SegLayout {
     global_idx = counts + align4((size_t)B * kCountWords);
     pad_idx = global_idx + bn;
     tiles = (N + kTileSlots - 1) / kTileSlots;
+    units = view_units(N);
     gunit = pad_idx + bn;
     view0 = gunit + (size_t)B * tiles * kUnitWords;
     perm = 0;
@@ -86,7 +95,7 @@ struct SegLayout {
     seg_of_tok = seg_off + align4((size_t)B * (N + 1));
     slot_rng = seg_of_tok + bn;
     unit = slot_rng + align4((size_t)B * N * 2);
-    view_stride = unit + (size_t)B * (tiles + 2) * kUnitWords;
+    view_stride = unit + (size_t)B * units * kUnitWords;
     total = view0 + 2 * view_stride;
   }
 };
@@ -101,9 +110,9 @@ struct SegTables {
   const int* seg_off[2];  // [B][N+1]
   const int* seg_of_tok[2];
   const int2* slot_rng[2];  // [B][N]
-  const int4* unit[2];    // [B][tiles + 2][2]
+  const int4* unit[2];    // [B][units][2]
   const int4* gunit;      // [B][tiles][2]
-  int tiles;
+  int tiles, units;
 };
 
 inline SegTables make_tables(const void* segments, int B, int N) {
@@ -124,6 +133,7 @@ inline SegTables make_tables(const void* segments, int B, int N) {
   }
   t.gunit = reinterpret_cast<const int4*>(w + L.gunit);
   t.tiles = L.tiles;
+  t.units = L.units;
   return t;
 }
 

@@ -9,10 +9,11 @@
 // digits inside a 64-element batch in lane order with ballots), so ties keep ascending position.
 // Passes whose digit is zero for every id are skipped: ids below 512 cost one pass.
 //
-// The kernel also lists the work units of the attention kernels per (sequence, view): for every
-// 128-slot tile of the sorted order the window of sorted slots its segments span, then the pad
-// tiles, and per sequence the chunks of the question-token owners.  The attention kernels map
-// a workgroup index to one of these records with arithmetic alone.
+// The kernel also lists the work units of the attention kernels per (sequence, view): pieces of
+// up to 128 slots of the sorted order (cut so that none straddles the boundary of a long
+// segment, listed longest streamed side first) with the window of sorted slots their segments
+// span, then the pad tiles, and per sequence the chunks of the question-token owners.  The
+// attention kernels map a workgroup index to one of these records with arithmetic alone.
 //
 // Bucketed mode (the approximation of Section 3.1: a global part of at most G tokens, the rest
 // of the head's order in buckets of R, a bucket meeting itself and its two neighbours): the
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   int* seg_off = vbase + lay.seg_off + (size_t)b * (N + 1);
   int* seg_of_tok = vbase + lay.seg_of_tok + (size_t)b * N;
   int2* slot_rng = reinterpret_cast<int2*>(vbase + lay.slot_rng) + (size_t)b * N;
-  int4* unit = reinterpret_cast<int4*>(vbase + lay.unit) + (size_t)b * (lay.tiles + 2) * 2;
+  int4* unit = reinterpret_cast<int4*>(vbase + lay.unit) + (size_t)b * lay.units * 2;
   int4* gunit = reinterpret_cast<int4*>(seg + lay.gunit) + (size_t)b * lay.tiles * 2;
   const int* id_src = (view == 0 ? row_ids : col_ids) + (size_t)b * N;
   const unsigned char* fl = flags + (size_t)b * N;
@@ -351,21 +352,109 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   }
 
   // ---- work units of the attention kernels -------------------------------------------------
-  // table-token owners: 128 sorted slots each, streaming the question tokens and then the slot
-  // window spanned by the segments those slots touch; pad owners after them
-  const int n_lt = (L + kTileSlots - 1) / kTileSlots, n_pt = (P + kPadSlots - 1) / kPadSlots;
+  // Table-token owners: up to 128 consecutive sorted slots each, streaming the question tokens
+  // and then the slot window spanned by the segments those slots touch; pad owners after them.
+  // A segment of at least kBigSegment slots starts a unit of its own ("cut"), and so does the
+  // first slot after it, so no unit straddles the boundary of a long segment; if that would
+  // need more records than the buffer has, the slots are cut every 128 regardless.
+  const int n_pt = (P + kPadSlots - 1) / kPadSlots;
   const int n_t0 = (G + BN - 1) / BN;
-  if (tid < lay.tiles + 2) {
-    int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
-    if (tid < n_lt) {
-      const int t0 = tid * kTileSlots, lo = window(t0).x, hi = window(min(t0 + kTileSlots, L) - 1).y;
-      r0 = make_int4(UNIT_LOCAL, t0, lo, hi);
-      r1.y = n_t0 + (hi - lo + BN - 1) / BN;
-    } else if (tid < n_lt + n_pt) {
-      r0 = make_int4(UNIT_PAD, (tid - n_lt) * kPadSlots, 0, 0);
+  constexpr int kMaxUnits = kMaxTiles + kMaxTiles / 2 + 2;
+  __shared__ unsigned short head_pos[kMaxUnits];
+  __shared__ unsigned short unit_len[kMaxUnits];
+  auto seg_size = [&](int g) { return (g + 1 < S ? (int)seg_start[g + 1] : L) - (int)seg_start[g]; };
+  unsigned cut_bits = 0;  // bit e: my slot of batch e is a cut
+#pragma unroll
+  for (int e = 0; e < NB; ++e) {
+    const int s = w0 + e * 64 + lane;
+    bool cut = false;
+    if (s < L) {
+      const int g = seg_of_slot[s];
+      cut = s == (int)seg_start[g] &&
+            (g == 0 || seg_size(g) >= kBigSegment || seg_size(g - 1) >= kBigSegment);
     }
-    unit[2 * tid] = r0;
-    unit[2 * tid + 1] = r1;
+    cut_bits |= (unsigned)cut << e;
+  }
+  int n_units = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {  // 0: with cuts; 1: every 128 slots (rare)
+    const bool use_cuts = attempt == 0;
+    // last cut inside each wavefront's block -> the cut in force at the start of the next ones
+    int last = -1;
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const unsigned long long m = __ballot(use_cuts && ((cut_bits >> e) & 1u));
+      if (m) last = w0 + e * 64 + 63 - __clzll((long long)m);
+    }
+    if (lane == 0) wave_tot[1][wave] = last;
+    lds_barrier();
+    int running = 0;
+#pragma unroll
+    for (int w = 0; w < kSegWaves; ++w)
+      if (w < wave) running = max(running, wave_tot[1][w]);
+    unsigned hbits = 0;  // bit e: my slot of batch e starts a unit
+    int n_head_w = 0;
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      const int s = w0 + e * 64 + lane;
+      const unsigned long long m = __ballot(use_cuts && ((cut_bits >> e) & 1u));
+      const unsigned long long upto = m & (~0ull >> (63 - lane));  // cuts at lanes <= mine
+      const int base = upto ? w0 + e * 64 + 63 - __clzll((long long)upto) : running;
+      const bool head = s < L && ((s - base) & (kTileSlots - 1)) == 0;
+      hbits |= (unsigned)head << e;
+      n_head_w += __popcll(__ballot(head));
+      if (m) running = w0 + e * 64 + 63 - __clzll((long long)m);
+    }
+    if (lane == 0) wave_tot[0][wave] = n_head_w;
+    lds_barrier();
+    int head_at = 0;
+    n_units = 0;
+#pragma unroll
+    for (int w = 0; w < kSegWaves; ++w) {
+      const int c = wave_tot[0][w];
+      if (w < wave) head_at += c;
+      n_units += c;
+    }
+    const bool fits = n_units + n_pt <= lay.units;  // always true without cuts
+    if (fits) {
+#pragma unroll
+      for (int e = 0; e < NB; ++e) {
+        const bool head = (hbits >> e) & 1u;
+        const unsigned long long mh = __ballot(head);
+        if (head) head_pos[head_at + lanes_before(mh)] = (unsigned short)(w0 + e * 64 + lane);
+        head_at += __popcll(mh);
+      }
+    }
+    lds_barrier();  // head_pos is complete; wave_tot may be written again
+    if (fits) break;
+  }
+  // streamed length of every unit, then its place in the list: longest first (ties in slot
+  // order), so that across a launch the long units start first and the short ones fill the end
+  int4 r0 = make_int4(UNIT_NONE, 0, 0, 0), r1 = make_int4(0, 0, -1, 0);
+  if (tid < n_units) {
+    // (clamped so that a record can never name a slot outside [0, L), whatever else goes wrong)
+    const int t0 = min((int)head_pos[tid], L - 1);
+    const int end = min(max(tid + 1 < n_units ? (int)head_pos[tid + 1] : L, t0 + 1), min(L, t0 + kTileSlots));
+    const int lo = window(t0).x, hi = window(end - 1).y;
+    r0 = make_int4(UNIT_LOCAL, t0, lo, hi);
+    r1.y = n_t0 + (hi - lo + BN - 1) / BN;
+    r1.w = end;
+    unit_len[tid] = (unsigned short)r1.y;
+  }
+  lds_barrier();
+  if (tid < lay.units) {
+    int place = tid;
+    if (tid < n_units) {
+      place = 0;
+      const int mine = r1.y;
+      for (int j = 0; j < n_units; ++j) {
+        const int other = unit_len[j];
+        place += other > mine || (other == mine && j < tid);
+      }
+    } else if (tid < n_units + n_pt) {
+      r0 = make_int4(UNIT_PAD, (tid - n_units) * kPadSlots, 0, 0);
+    }
+    unit[2 * place] = r0;
+    unit[2 * place + 1] = r1;
   }
   // question-token owners (the same for both views; written by the row view's workgroup)
   if (view == 0 && tid < lay.tiles) {

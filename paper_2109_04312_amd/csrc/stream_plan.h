@@ -6,8 +6,8 @@
 // own row / column segment; an owned question token meets every non-pad token.
 //
 // Units of one (sequence, head) -- listed by the segment builder, see seg_layout.h:
-//   local   ceil(L / 128) table-token owners, 128 consecutive slots of the head kind's sorted
-//           order
+//   local   table-token owners, up to 128 consecutive slots of the head kind's sorted order
+//           that never straddle the boundary of a long segment; listed longest stream first
 //   pad     ceil(P / 1024) pad owners (zero fill)
 //   global  question-token owners.  Their streamed side is the whole sequence, so it is cut into
 //           chunks that run as separate units and leave partial results, merged by a finalize
@@ -17,11 +17,12 @@
 // consecutive XCDs, so a queue stays on one XCD and the units of one (sequence, head) pair
 // share an L2).  Column-head pairs are numbered c = b n_col + i and belong to queue c mod 8, row-
 // head pairs r = b n_row + i to queue (r + B n_col) mod 8.  Order inside a queue, longest units first:
-//   1. column heads: table-token (then pad) tile 0 of every pair, tile 1 of every pair, ...
-//   2. the first quarter of the question-token unit records of all pairs, the same way (all
-//      of the real ones unless most of the sequence is question tokens)
+//   1. column heads: record 0 (the longest unit) of every pair, record 1 of every pair, ... up
+//      to record T - 1
+//   2. the first T / 8 + 2 question-token unit records of all pairs, the same way (all of the
+//      real ones unless a sequence has more than 128 question tokens)
 //   3. row heads, as in 1
-//   4. the remaining question-token unit records
+//   4. what is left of the three lists (real records only in the cases named above)
 // Records of kind "none" pad every pair to the same count; their workgroups exit at once.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -54,8 +55,8 @@ struct Work {
 };
 
 inline int unit_grid(int B, int H, int N, int n_col) {
-  const int T = owner_slots(N), nc = (B * n_col + 7) / 8, nr = (B * (H - n_col) + 7) / 8;
-  return 8 * ((nc + nr) * (T + 2) + (nc + nr) * T);
+  const int T = owner_slots(N), U = view_units(N), nc = (B * n_col + 7) / 8, nr = (B * (H - n_col) + 7) / 8;
+  return 8 * ((nc + nr) * U + (nc + nr) * T);
 }
 
 // Entry i of the head order.  A byte indexed by a run-time value would be fetched with a vector
@@ -69,35 +70,36 @@ __device__ inline int head_at(const AttnArgs& a, int i) {
 // Returns false if this workgroup has nothing to do.  Everything here is wave-uniform and
 // stays in scalar registers.
 __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
-  const int T = a.seg.tiles, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
+  const int T = a.seg.tiles, U = a.seg.units, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
   const int q = blockIdx.x & 7;
   // row-head pairs are dealt to the queues starting where the column-head pairs stopped, so that
   // a handful of pairs still spreads over as many XCDs as possible
   const int qr = (q - a.B * n_col) & 7;
   const int nc = (a.B * n_col - q + 7) >> 3, nr = (a.B * n_row - qr + 7) >> 3;  // pairs of this queue
-  const int T1 = (T + 3) >> 2;  // question-token units per pair in the early part of their list
+  // Records are listed longest first and the empty ones last, and how many are real is only
+  // known on the device: a workgroup that finds an empty record leaves at once, but it still
+  // took a slot for a microsecond, and a thousand of them ahead of real units delay those by
+  // several.  So the early part of each list (where the real records are unless a sequence is
+  // filled to the last position, resp. has more than 128 question tokens) comes first for all
+  // three kinds of unit, the remainders after them.
+  const int E = min(U, T), T1 = min(T, (T >> 3) + 2);
   int t = blockIdx.x >> 3;
   // region -> (first pair, pairs, first record, records per pair)
-  int first = 0, pairs = nc, k0 = 0, per = T + 2;
+  int first = 0, pairs = nc, k0 = 0, per = E;
   bool glob = false;
-  if (t >= nc * (T + 2)) {
-    t -= nc * (T + 2);
-    pairs = nc + nr;
-    per = T1;
-    glob = true;
-    if (t >= pairs * T1) {
-      t -= pairs * T1;
-      first = nc;
-      pairs = nr;
-      per = T + 2;
-      glob = false;
-      if (t >= nr * (T + 2)) {
-        t -= nr * (T + 2);
-        first = 0;
-        pairs = nc + nr;
-        k0 = T1;
-        per = T - T1;
-        glob = true;
+  const int n_all = nc + nr;
+  if (t >= nc * E) {                       // question-token owners, early part
+    t -= nc * E; first = 0; pairs = n_all; k0 = 0; per = T1; glob = true;
+    if (t >= n_all * T1) {                 // row heads, early part
+      t -= n_all * T1; first = nc; pairs = nr; k0 = 0; per = E; glob = false;
+      if (t >= nr * E) {                   // column heads, rest
+        t -= nr * E; first = 0; pairs = nc; k0 = E; per = U - E;
+        if (t >= nc * (U - E)) {           // row heads, rest
+          t -= nc * (U - E); first = nc; pairs = nr;
+          if (t >= nr * (U - E)) {         // question-token owners, rest
+            t -= nr * (U - E); first = 0; pairs = n_all; k0 = T1; per = T - T1; glob = true;
+          }
+        }
       }
     }
   }
@@ -121,7 +123,7 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   }
   w.bh = b * a.H + h;
   const int4* rec = glob ? a.seg.gunit + ((size_t)b * T + k) * 2
-                         : a.seg.unit[w.view] + ((size_t)b * (T + 2) + k) * 2;
+                         : a.seg.unit[w.view] + ((size_t)b * U + k) * 2;
   // The header is fetched together with the record (one scalar round trip for both): tables
   // built for another (B, N), or never built, make every workgroup leave before it uses a word
   // of them.  All of these reads stay inside the mate_segments_bytes(B, N) bytes the caller
@@ -147,7 +149,7 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   u.str_list = glob ? a.seg.perm[0] + (size_t)b * N : perm_v;  // row order: the contiguous one
   u.own_list = glob ? a.seg.global_idx + (size_t)b * N
                     : u.kind == UNIT_LOCAL ? perm_v : a.seg.pad_idx + (size_t)b * N;
-  u.own_count = glob ? u.G : u.kind == UNIT_LOCAL ? u.L : u.P;
+  u.own_count = glob ? u.G : u.kind == UNIT_LOCAL ? r1.w : u.P;
   return true;
 }
 
