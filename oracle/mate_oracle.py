@@ -32,6 +32,9 @@ What each function follows in the paper (arXiv 2109.04312):
                            and the usual output projection over the concatenated heads (the
                            equation stops at the head; the model is a standard Transformer
                            layer otherwise).
+  * project_qkv_backward, project_out_backward
+                        -- not in the paper: the derivatives of the two projections with
+                           respect to their input, weights and bias.
 
 Readings taken where the paper is silent (listed again in the design notes):
   * the softmax scale is an explicit argument (the equation has none, the appendix
@@ -331,3 +334,39 @@ def project_out(o, w_o, bias, flags):
     if bias is not None:
         y = y + np.asarray(bias, np.float64)
     return y * (np.asarray(flags) != TOK_PAD)[:, :, None]
+
+
+def project_qkv_backward(x, w_qkv, flags, dq, dk, dv, n_heads):
+    """Derivative of project_qkv: with Y = [q | k | v] (all heads, feature order as the rows of
+    w_qkv) and G = dL/dY assembled from dq, dk, dv [B,H,N,m] (rows of pad tokens ignored: the
+    forward writes zeros there whatever x is), returns
+      dx [B,N,E]      = G w_qkv           (0 at pad tokens)
+      dw [3*H*m, E]   = sum over non-pad tokens of G^T x
+      dbias [3*H*m]   = sum over non-pad tokens of G."""
+    x = np.asarray(x, np.float64)
+    w = np.asarray(w_qkv, np.float64)
+    B, N, E = x.shape
+    keep = (np.asarray(flags) != TOK_PAD)[:, :, None]
+    g = np.concatenate([np.asarray(t, np.float64).transpose(0, 2, 1, 3).reshape(B, N, -1) for t in (dq, dk, dv)],
+                       axis=-1) * keep                                  # [B,N,3*H*m]
+    dx = g @ w
+    g2 = g.reshape(B * N, -1)
+    dw = g2.T @ x.reshape(B * N, E)
+    return dx, dw, g2.sum(axis=0)
+
+
+def project_out_backward(o, w_o, flags, dy):
+    """Derivative of project_out: with G = dy [B,N,E] (rows of pad tokens ignored), returns
+      d_o [B,H,N,m]  = G w_o, split back into heads (0 at pad tokens)
+      dw [E, H*m]    = sum over non-pad tokens of G^T concat_i o[:, i]
+      dbias [E]      = sum over non-pad tokens of G."""
+    o = np.asarray(o, np.float64)
+    w = np.asarray(w_o, np.float64)
+    B, H, N, m = o.shape
+    g = np.asarray(dy, np.float64) * (np.asarray(flags) != TOK_PAD)[:, :, None]
+    cat = o.transpose(0, 2, 1, 3).reshape(B, N, H * m)
+    d_cat = g @ w                                                        # [B,N,H*m]
+    d_o = np.ascontiguousarray(d_cat.reshape(B, N, H, m).transpose(0, 2, 1, 3))
+    g2 = g.reshape(B * N, -1)
+    dw = g2.T @ cat.reshape(B * N, H * m)
+    return d_o, dw, g2.sum(axis=0)
