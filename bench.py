@@ -214,8 +214,8 @@ def breakeven(steps, warmup):
 
 
 def projections(cfg, steps, warmup):
-    """Times mate_qkv_project and mate_out_project on a configuration's layer shape (model width
-    64 * H) with HIP events recorded by the library around each launch."""
+    """Times the projection kernels, forward and backward, on a configuration's layer shape (model
+    width 64 * H) with HIP events recorded by the library around each launch."""
     import ctypes as C
     import torch
     from paper_2109_04312_amd import mate, synth
@@ -233,6 +233,8 @@ def projections(cfg, steps, warmup):
     fl = torch.from_numpy(st.flags).cuda()
     q, k, v = (torch.empty((B, H, N, 64), dtype=torch.bfloat16, device="cuda") for _ in range(3))
     y = torch.empty((B, N, E), dtype=torch.bfloat16, device="cuda")
+    dy = torch.randn((B, N, E), device="cuda", generator=g).to(torch.bfloat16)
+    ws = mate.project_bwd_workspace(B, N, H, E, "cuda")
     hip = C.CDLL("libamdhip64.so")
 
     def new_event():
@@ -244,34 +246,50 @@ def projections(cfg, steps, warmup):
         mate.qkv_project(x, w_qkv, b_qkv, fl, H, q=q, k=k, v=v)
         mate.out_project(q, w_o, b_o, fl, y=y)
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    both = (time.perf_counter() - t0) / steps
+    def step_bwd():   # gradients of the same two calls (q, k, v stand in for dq, dk, dv and for o)
+        mate.out_project_bwd(q, w_o, fl, dy, ws=ws)
+        mate.qkv_project_bwd(x, w_qkv, fl, q, k, v, ws=ws)
+
+    def wall(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    both, both_bwd = wall(step), wall(step_bwd)
     res = {}
-    for name, kid in (("qkv_project", mate.MATE_KERNEL_QKV_PROJECT), ("out_project", mate.MATE_KERNEL_OUT_PROJECT)):
+    for name, kid, fn in (("qkv_project", mate.MATE_KERNEL_QKV_PROJECT, step),
+                          ("out_project", mate.MATE_KERNEL_OUT_PROJECT, step),
+                          ("qkv_project_dgrad", mate.MATE_KERNEL_QKV_PROJECT_DGRAD, step_bwd),
+                          ("qkv_project_wgrad", mate.MATE_KERNEL_QKV_PROJECT_WGRAD, step_bwd),
+                          ("out_project_dgrad", mate.MATE_KERNEL_OUT_PROJECT_DGRAD, step_bwd),
+                          ("out_project_wgrad", mate.MATE_KERNEL_OUT_PROJECT_WGRAD, step_bwd)):
         evs = [(new_event(), new_event()) for _ in range(steps)]
         for e0, e1 in evs:
             assert mate.mate_profile_kernel(kid, e0, e1) == 0
-            step()
+            fn()
         torch.cuda.synchronize()
-        tot = 0.0
+        samples = []
         for e0, e1 in evs:
             ms = C.c_float()
             assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
-            tot += ms.value
-        res[name] = tot / steps * 1e-3
+            samples.append(ms.value * 1e-3)
+        samples.sort()
+        res[name] = samples[len(samples) // 2]
     nonpad = int((st.flags != synth.TOK_PAD).sum())
-    flop = {"qkv_project": 2.0 * nonpad * E * 3 * E, "out_project": 2.0 * nonpad * E * E}
-    out = {"projections": {n: {"us": t * 1e6, "algorithmic_flop": flop[n], "achieved_tflops": flop[n] / t / 1e12,
+    big, small = 2.0 * nonpad * E * 3 * E, 2.0 * nonpad * E * E
+    flop = {"qkv_project": big, "out_project": small, "qkv_project_dgrad": big, "qkv_project_wgrad": big,
+            "out_project_dgrad": small, "out_project_wgrad": small}
+    out = {"projections": {n: {"median_us": t * 1e6, "algorithmic_flop": flop[n], "achieved_tflops": flop[n] / t / 1e12,
                                "frac_of_bf16_mfma_peak": flop[n] / t / 1e12 / PEAK_BF16_TFLOPS} for n, t in res.items()},
            "workload": w.name, "B": B, "N": N, "H": H, "E": E, "non_pad_tokens": nonpad, "dtype": "bf16",
-           "us_both_wall": both * 1e6, "steps": steps,
-           "flop_convention": "2 * non-pad tokens * K * F (pad rows are not algorithmic work)"}
+           "us_forward_wall": both * 1e6, "us_backward_wall": both_bwd * 1e6, "steps": steps,
+           "backward_wall_includes": "weight transposes and pad masks (preparation kernel), partial-sum finalize kernels",
+           "flop_convention": "2 * non-pad tokens * K * F per product (pad rows are not algorithmic work)"}
     print(json.dumps(out))
 
 

@@ -302,6 +302,38 @@ mate_status mate_out_project(const void* o, const void* w_o, const float* bias,
                              void* y, void* stream);
 
 /*
+ * Backward of the two projections (the derivative of the calls above; the paper trains through
+ * them but does not write them out), bf16 on the matrix cores with fp32 accumulation.
+ *
+ * mate_qkv_project_bwd:  with G[b,k,:] = the rows of dq, dk, dv at token (b,k) in the feature order
+ * of w_qkv (rows of PAD tokens count as zero, whatever they hold),
+ *     dx[b,k,:]  = G[b,k,:] w_qkv                      [B, N, E] bf16, rows of PAD tokens written 0
+ *     dw_qkv     = sum over non-pad tokens of G^T x    [3*H*64, E] float
+ *     dbias      = sum over non-pad tokens of G        [3*H*64] float
+ *   dq, dk, dv are read in the [B, H, N, 64] layout mate_attn_bwd writes them in.
+ * mate_out_project_bwd:  with G = dy [B, N, E] (rows of PAD tokens count as zero),
+ *     d_o[b,i,k,:] = (G[b,k,:] w_o)[64 i .. 64 i + 63] [B, H, N, 64] bf16, the layout mate_attn_bwd
+ *                                                      reads dout in; rows of PAD tokens written 0
+ *     dw_o       = sum over non-pad tokens of G^T concat_i o[b,i,k,:]    [E, H*64] float
+ *     dbias      = sum over non-pad tokens of G        [E] float
+ *
+ *   dx / d_o, dw_*, dbias   any of them may be NULL (not computed); dbias needs dw_*
+ *   workspace   mate_project_bwd_workspace_bytes(B, N, H, E) bytes (a transposed copy of the
+ *               weights, one 64-bit pad mask per 64 tokens, partial sums of the weight gradient)
+ *   t, H, E     as for the forward calls
+ * Asynchronous on `stream`; deterministic (partial sums are added in a fixed order, no atomics).
+ */
+size_t mate_project_bwd_workspace_bytes(int B, int N, int H, int E);
+mate_status mate_qkv_project_bwd(const void* x, const void* w_qkv, const uint8_t* flags,
+                                 const void* dq, const void* dk, const void* dv, int B, int N,
+                                 int H, int E, mate_dtype t, void* dx, float* dw_qkv, float* dbias,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+mate_status mate_out_project_bwd(const void* o, const void* w_o, const uint8_t* flags,
+                                 const void* dy, int B, int N, int H, int E, mate_dtype t,
+                                 void* d_o, float* dw_o, float* dbias, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hook, not part of the computation: arms the calling thread so that the next
  * launch of the named kernel (inside mate_build_segments / mate_attn_fwd* / mate_attn_bwd* /
  * mate_*_project) is
@@ -312,7 +344,9 @@ mate_status mate_out_project(const void* o, const void* w_o, const float* bias,
  */
 enum { MATE_KERNEL_NONE = 0, MATE_KERNEL_BUILD = 1, MATE_KERNEL_FWD = 2, MATE_KERNEL_BWD_DQ = 3,
        MATE_KERNEL_BWD_DKV = 4, MATE_KERNEL_FWD_DENSE = 5, MATE_KERNEL_BWD_DQ_DENSE = 6,
-       MATE_KERNEL_BWD_DKV_DENSE = 7, MATE_KERNEL_QKV_PROJECT = 8, MATE_KERNEL_OUT_PROJECT = 9 };
+       MATE_KERNEL_BWD_DKV_DENSE = 7, MATE_KERNEL_QKV_PROJECT = 8, MATE_KERNEL_OUT_PROJECT = 9,
+       MATE_KERNEL_QKV_PROJECT_DGRAD = 10, MATE_KERNEL_QKV_PROJECT_WGRAD = 11,
+       MATE_KERNEL_OUT_PROJECT_DGRAD = 12, MATE_KERNEL_OUT_PROJECT_WGRAD = 13 };
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event);
 
 /*

@@ -239,6 +239,39 @@ mate_status mate_out_project(const void* o, const void* w_o, const float* bias,
   return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
 }
 
+size_t mate_project_bwd_workspace_bytes(int B, int N, int H, int E) {
+  if (proj_args_ok(B, N, H, E, MATE_BF16) != MATE_OK) return 0;
+  return std::max(qkv_project_bwd_workspace(B, N, H, E), out_project_bwd_workspace(B, N, H, E));
+}
+
+mate_status mate_qkv_project_bwd(const void* x, const void* w_qkv, const uint8_t* flags,
+                                 const void* dq, const void* dk, const void* dv, int B, int N,
+                                 int H, int E, mate_dtype t, void* dx, float* dw_qkv, float* dbias,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !w_qkv || !flags || !dq || !dk || !dv) return MATE_ERR_NULL;
+  const mate_status st = proj_args_ok(B, N, H, E, t);
+  if (st != MATE_OK) return st;
+  if (dbias && !dw_qkv) return MATE_ERR_NULL;  // the bias gradient rides on the weight gradient
+  if (!workspace || workspace_bytes < qkv_project_bwd_workspace(B, N, H, E)) return MATE_ERR_WORKSPACE;
+  hipError_t e = launch_qkv_project_bwd(x, w_qkv, flags, dq, dk, dv, B, N, H, E, dx, dw_qkv, dbias,
+                                        workspace, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
+mate_status mate_out_project_bwd(const void* o, const void* w_o, const uint8_t* flags,
+                                 const void* dy, int B, int N, int H, int E, mate_dtype t,
+                                 void* d_o, float* dw_o, float* dbias, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!o || !w_o || !flags || !dy) return MATE_ERR_NULL;
+  const mate_status st = proj_args_ok(B, N, H, E, t);
+  if (st != MATE_OK) return st;
+  if (dbias && !dw_o) return MATE_ERR_NULL;
+  if (!workspace || workspace_bytes < out_project_bwd_workspace(B, N, H, E)) return MATE_ERR_WORKSPACE;
+  hipError_t e = launch_out_project_bwd(o, w_o, flags, dy, B, N, H, E, d_o, dw_o, dbias, workspace,
+                                        static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MATE_OK : MATE_ERR_HIP;
+}
+
 mate_status mate_attn_fwd(const void* q, const void* k, const void* v, const void* segments,
                           const uint8_t* head_kind, int B, int H, int N, int D, mate_dtype t,
                           float scale, void* out, float* lse, void* workspace,
@@ -387,7 +420,7 @@ mate_status mate_attn_bwd_dense_static(const void* q, const void* k, const void*
 }
 
 mate_status mate_profile_kernel(int kernel, void* start_event, void* stop_event) {
-  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_OUT_PROJECT) return MATE_ERR_UNSUPPORTED;
+  if (kernel < MATE_KERNEL_NONE || kernel > MATE_KERNEL_OUT_PROJECT_WGRAD) return MATE_ERR_UNSUPPORTED;
   if (kernel != MATE_KERNEL_NONE && (!start_event || !stop_event)) return MATE_ERR_NULL;
   g_profile_hook.kernel = kernel;
   g_profile_hook.start = static_cast<hipEvent_t>(start_event);

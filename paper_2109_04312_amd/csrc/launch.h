@@ -82,6 +82,18 @@ hipError_t launch_out_project(const void* o, const void* w_o, const float* bias,
                               const unsigned char* flags, int B, int N, int H, int E, void* y,
                               hipStream_t stream);
 
+// Backward of the two projections.  dx / d_o, dw, dbias may each be null (not wanted); dw and
+// dbias are float32.  `workspace` holds *_project_bwd_workspace(...) bytes.
+size_t qkv_project_bwd_workspace(int B, int N, int H, int E);
+size_t out_project_bwd_workspace(int B, int N, int H, int E);
+hipError_t launch_qkv_project_bwd(const void* x, const void* w_qkv, const unsigned char* flags,
+                                  const void* dq, const void* dk, const void* dv, int B, int N, int H,
+                                  int E, void* dx, float* dw, float* dbias, void* workspace,
+                                  hipStream_t stream);
+hipError_t launch_out_project_bwd(const void* o, const void* w_o, const unsigned char* flags,
+                                  const void* dy, int B, int N, int H, int E, void* d_o, float* dw,
+                                  float* dbias, void* workspace, hipStream_t stream);
+
 // Measurement aid: `workgroups` x 4 wavefronts each issue `iters` x 8 independent 32x32x16 bf16
 // MFMAs and write one float per thread to `sink` (workgroups * 256 floats).
 hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t stream);

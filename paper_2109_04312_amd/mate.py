@@ -27,12 +27,14 @@ MATE_MAX_N, MATE_MAX_HEADS, MATE_HEAD_DIM = 16384, 256, 64
 
 EXPORTS = ["mate_segments_bytes", "mate_workspace_bytes", "mate_build_segments",
            "mate_build_segments_bucketed", "mate_cell_positions", "mate_segments_export", "mate_segments_export_windows", "mate_attn_fwd", "mate_attn_bwd", "mate_dense_workspace_bytes",
-           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_attn_bwd_dense_static", "mate_attn_prefers_dense", "mate_segments_status", "mate_qkv_project", "mate_out_project", "mate_profile_kernel",
+           "mate_attn_fwd_dense", "mate_attn_bwd_dense", "mate_attn_bwd_dense_static", "mate_attn_prefers_dense", "mate_segments_status", "mate_qkv_project", "mate_out_project", "mate_project_bwd_workspace_bytes", "mate_qkv_project_bwd", "mate_out_project_bwd", "mate_profile_kernel",
            "mate_probe_mfma", "mate_status_string"]
 MATE_KERNEL_NONE, MATE_KERNEL_BUILD, MATE_KERNEL_FWD = 0, 1, 2
 MATE_KERNEL_BWD_DQ, MATE_KERNEL_BWD_DKV = 3, 4
 MATE_KERNEL_FWD_DENSE, MATE_KERNEL_BWD_DQ_DENSE, MATE_KERNEL_BWD_DKV_DENSE = 5, 6, 7
 MATE_KERNEL_QKV_PROJECT, MATE_KERNEL_OUT_PROJECT = 8, 9
+MATE_KERNEL_QKV_PROJECT_DGRAD, MATE_KERNEL_QKV_PROJECT_WGRAD = 10, 11
+MATE_KERNEL_OUT_PROJECT_DGRAD, MATE_KERNEL_OUT_PROJECT_WGRAD = 12, 13
 MATE_DENSE_MAX_N = 1024
 MATE_DENSE_PREFERRED_MAX_N = 256
 
@@ -79,6 +81,12 @@ _lib.mate_qkv_project.restype = _i
 _lib.mate_qkv_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p, _p, _p]
 _lib.mate_out_project.restype = _i
 _lib.mate_out_project.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p]
+_lib.mate_project_bwd_workspace_bytes.restype = _sz
+_lib.mate_project_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i]
+_lib.mate_qkv_project_bwd.restype = _i
+_lib.mate_qkv_project_bwd.argtypes = [_p, _p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p, _p, _p, _sz, _p]
+_lib.mate_out_project_bwd.restype = _i
+_lib.mate_out_project_bwd.argtypes = [_p, _p, _p, _p, _i, _i, _i, _i, _i, _p, _p, _p, _p, _sz, _p]
 _lib.mate_profile_kernel.restype = _i
 _lib.mate_profile_kernel.argtypes = [_i, _p, _p]
 _lib.mate_probe_mfma.restype = _i
@@ -106,6 +114,9 @@ mate_attn_bwd_dense_static = _lib.mate_attn_bwd_dense_static
 MATE_STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
 mate_qkv_project = _lib.mate_qkv_project
 mate_out_project = _lib.mate_out_project
+mate_project_bwd_workspace_bytes = _lib.mate_project_bwd_workspace_bytes
+mate_qkv_project_bwd = _lib.mate_qkv_project_bwd
+mate_out_project_bwd = _lib.mate_out_project_bwd
 
 
 def mate_status_string(status: int) -> str:
@@ -320,6 +331,50 @@ def out_project(o, w_o, bias, flags, y=None):
                             _dev(flags, "flags"), B, N, H, E, MATE_BF16, _dev(y, "y"), _stream()),
            "mate_out_project")
     return y
+
+
+def _opt(t, name):
+    return _dev(t, name) if t is not None else None
+
+
+def project_bwd_workspace(B, N, H, E, device) -> torch.Tensor:
+    n = mate_project_bwd_workspace_bytes(B, N, H, E)
+    if n == 0:
+        raise MateError(MATE_ERR_UNSUPPORTED, "mate_project_bwd_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def qkv_project_bwd(x, w_qkv, flags, dq, dk, dv, want_dx=True, want_dw=True, want_dbias=True, ws=None):
+    """Gradients of qkv_project: dx [B,N,E] bf16, dw_qkv [3*H*64,E] float32, dbias [3*H*64] float32
+    (None for the ones not wanted)."""
+    B, N, E = x.shape
+    H = dq.shape[1]
+    assert x.dtype == torch.bfloat16 and w_qkv.shape == (3 * H * 64, E) and dq.shape == (B, H, N, 64)
+    assert dk.shape == dq.shape and dv.shape == dq.shape and flags.shape == (B, N)
+    dx = torch.empty_like(x) if want_dx else None
+    dw = torch.empty((3 * H * 64, E), dtype=torch.float32, device=x.device) if want_dw else None
+    db = torch.empty(3 * H * 64, dtype=torch.float32, device=x.device) if want_dbias else None
+    ws = project_bwd_workspace(B, N, H, E, x.device) if ws is None else ws
+    _check(mate_qkv_project_bwd(_dev(x, "x"), _dev(w_qkv, "w_qkv"), _dev(flags, "flags"), _dev(dq, "dq"),
+                                _dev(dk, "dk"), _dev(dv, "dv"), B, N, H, E, MATE_BF16, _opt(dx, "dx"),
+                                _opt(dw, "dw"), _opt(db, "dbias"), ws.data_ptr(), ws.numel(), _stream()),
+           "mate_qkv_project_bwd")
+    return dx, dw, db
+
+
+def out_project_bwd(o, w_o, flags, dy, want_do=True, want_dw=True, want_dbias=True, ws=None):
+    """Gradients of out_project: d_o [B,H,N,64] bf16, dw_o [E,H*64] float32, dbias [E] float32."""
+    B, H, N, D = o.shape
+    E = w_o.shape[0]
+    assert o.dtype == torch.bfloat16 and w_o.shape == (E, H * 64) and dy.shape == (B, N, E) and D == 64
+    d_o = torch.empty_like(o) if want_do else None
+    dw = torch.empty((E, H * 64), dtype=torch.float32, device=o.device) if want_dw else None
+    db = torch.empty(E, dtype=torch.float32, device=o.device) if want_dbias else None
+    ws = project_bwd_workspace(B, N, H, E, o.device) if ws is None else ws
+    _check(mate_out_project_bwd(_dev(o, "o"), _dev(w_o, "w_o"), _dev(flags, "flags"), _dev(dy, "dy"),
+                                B, N, H, E, MATE_BF16, _opt(d_o, "d_o"), _opt(dw, "dw"), _opt(db, "dbias"),
+                                ws.data_ptr(), ws.numel(), _stream()), "mate_out_project_bwd")
+    return d_o, dw, db
 
 
 def prefer_dense(B: int, H: int, N: int, dtype: torch.dtype = torch.bfloat16) -> bool:

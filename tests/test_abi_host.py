@@ -105,6 +105,29 @@ def test_argument_errors_of_the_later_entry_points(mate):
         assert op(*args) == want, (pos, val)
 
 
+def test_argument_errors_of_the_projection_backward(mate):
+    fake = 0x1000  # never dereferenced
+    assert mate.mate_project_bwd_workspace_bytes(2, 512, 12, 768) > 3 * 12 * 64 * 768 * 2
+    assert mate.mate_project_bwd_workspace_bytes(2, 512, 11, 768) == 0
+    assert mate.mate_project_bwd_workspace_bytes(2, 512, 12, 700) == 0
+    qb = mate.mate_qkv_project_bwd
+    ok = [fake, fake, fake, fake, fake, fake, 2, 512, 12, 768, mate.MATE_BF16, fake, fake, fake, fake, 1 << 40, None]
+    for pos, val, want in ((0, None, mate.MATE_ERR_NULL), (4, None, mate.MATE_ERR_NULL),
+                           (8, 11, mate.MATE_ERR_UNSUPPORTED), (10, mate.MATE_F32, mate.MATE_ERR_UNSUPPORTED),
+                           (7, 0, mate.MATE_ERR_SHAPE), (15, 16, mate.MATE_ERR_WORKSPACE),
+                           (14, None, mate.MATE_ERR_WORKSPACE), (12, None, mate.MATE_ERR_NULL)):
+        args = list(ok)
+        args[pos] = val
+        assert qb(*args) == want, (pos, val)
+    ob = mate.mate_out_project_bwd
+    ok = [fake, fake, fake, fake, 2, 512, 12, 768, mate.MATE_BF16, fake, fake, fake, fake, 1 << 40, None]
+    for pos, val, want in ((3, None, mate.MATE_ERR_NULL), (7, 64, mate.MATE_ERR_UNSUPPORTED),
+                           (13, 16, mate.MATE_ERR_WORKSPACE), (10, None, mate.MATE_ERR_NULL)):
+        args = list(ok)
+        args[pos] = val
+        assert ob(*args) == want, (pos, val)
+
+
 def test_choice_between_the_two_implementations(mate):
     """Section 3.1: the faster of the two equivalent implementations is used per case.  The
     library's choice is the measured break-even: bf16 up to MATE_DENSE_PREFERRED_MAX_N."""
