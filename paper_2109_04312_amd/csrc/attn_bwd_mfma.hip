@@ -21,6 +21,7 @@
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
+#include "tile_bodies.h"
 #include "tile_stream.h"
 
 namespace mate {
@@ -100,13 +101,7 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
   const float sc = a.scale * kLog2e;
 
   int koff[4], toff[2][2];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) koff[ks] = plain_off(m, hl, ks);
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
-    toff[db][0] = tr_off(lane, db, 0);
-    toff[db][1] = tr_off(lane, db, 1);
-  }
+  operand_offsets(lane, koff, toff);
 
   f32x16 dq_acc[2] = {zero16(), zero16()};
   for (int t = u.t_begin; t < u.t_end; ++t) {
@@ -117,39 +112,7 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-      const int d0 = base + 4 * hl - lo;
-      const unsigned len = (unsigned)(hi - lo);
-      // one 32-key block at a time, so only one block's scores are live
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          s = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s);     // S^T  = K Q^T
-          dp = mfma(read_plain(Vst + jb * 32 * 128, koff[ks]), gf[ks], dp);   // dP^T = V dO^T
-        }
-        // P = exp2(S sc - lse2); dS = P (dP - delta)
-#pragma unroll
-        for (int c = 0; c < 16; ++c)
-          s[c] = __builtin_amdgcn_exp2f(fmaf(s[c], sc, -lse2)) * (dp[c] - delta);
-        if (!full) {  // wave-uniform: zero the pairs outside the pattern
-#pragma unroll
-          for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + jb * 32 + 8 * (c >> 2) + (c & 3)) < len;
-            s[c] = in ? s[c] : 0.f;
-          }
-        }
-        // dQ^T += K^T dS^T
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 ds8 = pack8(s, 8 * tt);
-          const char* kt = Kst + (jb * 32 + tt * 16) * 128;
-#pragma unroll
-          for (int db = 0; db < 2; ++db)
-            dq_acc[db] = mfma(read_transposed(kt, toff[db][0], toff[db][1]), ds8, dq_acc[db]);
-        }
-      }
+      dq_tile(Kst, Vst, qf, gf, koff, toff, sc, lse2, delta, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), dq_acc);
     }
     stream.release();
   }
@@ -229,13 +192,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
                "v"(vf[2]), "v"(vf[3]));
 
   int poff[4], toff[2][2];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) poff[ks] = plain_off(m, hl, ks);
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
-    toff[db][0] = tr_off(lane, db, 0);
-    toff[db][1] = tr_off(lane, db, 1);
-  }
+  operand_offsets(lane, poff, toff);
 
   f32x16 dk_acc[2] = {zero16(), zero16()}, dv_acc[2] = {zero16(), zero16()};
   for (int t = u.t_begin; t < u.t_end; ++t) {
@@ -248,54 +205,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-      const int d0 = base + 4 * hl - lo;
-      const unsigned len = (unsigned)(hi - lo);
-      // one 32-query block at a time, so only one block's scores are live
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
-        // Rows of these tiles are the streamed queries.  The accumulators start at the rows'
-        // -lse / scale and -delta (from LDS, four consecutive rows per group of four
-        // registers), so the contractions deliver S - lse / scale and dP - delta directly.
-        f32x16 s, dp;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int row0 = ib * 32 + 8 * g + 4 * hl;
-          const float4 l4 = *reinterpret_cast<const float4*>(lse_row + row0);
-          const float4 d4 = *reinterpret_cast<const float4*>(delta_row + row0);
-          s[4 * g] = l4.x; s[4 * g + 1] = l4.y; s[4 * g + 2] = l4.z; s[4 * g + 3] = l4.w;
-          dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          s = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s);     // S  = Q K^T
-          dp = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp);   // dP = dO V^T
-        }
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          s[c] = __builtin_amdgcn_exp2f(s[c] * sc);  // P
-          dp[c] *= s[c];                             // dS
-        }
-        if (!full) {  // wave-uniform: zero the pairs outside the pattern
-#pragma unroll
-          for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + ib * 32 + 8 * (c >> 2) + (c & 3)) < len;
-            s[c] = in ? s[c] : 0.f;
-            dp[c] = in ? dp[c] : 0.f;
-          }
-        }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 p8 = pack8(s, 8 * tt), ds8 = pack8(dp, 8 * tt);
-          const char* gt = Gst + (ib * 32 + tt * 16) * 128;
-          const char* qt = Qst + (ib * 32 + tt * 16) * 128;
-#pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            dv_acc[db] = mfma(read_transposed(gt, toff[db][0], toff[db][1]), p8, dv_acc[db]);   // dV^T += dO^T P
-            dk_acc[db] = mfma(read_transposed(qt, toff[db][0], toff[db][1]), ds8, dk_acc[db]);  // dK^T += Q^T dS
-          }
-        }
-      }
+      dkv_tile(Qst, Gst, lse_row, delta_row, kf, vf, poff, toff, sc, hl, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), dk_acc, dv_acc);
     }
     stream.release();
   }

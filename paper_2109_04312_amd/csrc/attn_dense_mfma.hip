@@ -19,6 +19,7 @@
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
+#include "tile_bodies.h"
 
 namespace mate {
 namespace {
@@ -107,16 +108,25 @@ struct DenseStream {
   }
 };
 
-__device__ inline void operand_offsets(int lane, int (&poff)[4], int (&toff)[2][2]) {
-  const int m = lane & 31, hl = lane >> 5;
+// The dense-mask rule as a Mask of tile_bodies.h: the pair is kept iff the two tokens' codes say
+// so.  `codes` points at the tile's 64 codes in LDS, offset by this lane half's 4 hl.
+struct CodeMask {
+  static constexpr bool full = false;
+  const int* codes;
+  int my_code;
+  bool my_global;
+  int k[16];
+  __device__ __forceinline__ CodeMask(const int* tile_codes, int hl, int code, bool global)
+      : codes(tile_codes + 4 * hl), my_code(code), my_global(global) {}
+  __device__ __forceinline__ void load(int blk) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) poff[ks] = plain_off(m, hl, ks);
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
-    toff[db][0] = tr_off(lane, db, 0);
-    toff[db][1] = tr_off(lane, db, 1);
+    for (int g = 0; g < 4; ++g) {
+      const int4 kc = *reinterpret_cast<const int4*>(codes + blk * 32 + 8 * g);
+      k[4 * g] = kc.x; k[4 * g + 1] = kc.y; k[4 * g + 2] = kc.z; k[4 * g + 3] = kc.w;
+    }
   }
-}
+  __device__ __forceinline__ bool in(int, int c) const { return allowed(k[c], my_code, my_global); }
+};
 
 // ======================================================================================
 // forward
@@ -160,53 +170,7 @@ __global__ __launch_bounds__(kThreads) void fwd_dense_kernel(DenseArgs a) {
     const char* Kst = stream.acquire(t, n_tiles);
     const char* Vst = Kst + kTileBytes;
     if (!wave_active) continue;
-    f32x16 s[2] = {zero16(), zero16()};
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        s[jb] = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s[jb]);
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int4 kc = *reinterpret_cast<const int4*>(code + t * BN + jb * 32 + 8 * g + 4 * hl);
-        const int k4[4] = {kc.x, kc.y, kc.z, kc.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          s[jb][4 * g + r] = allowed(k4[r], me.code, me.global) ? s[jb][4 * g + r] : -INFINITY;
-      }
-    float mx = s[0][0];
-#pragma unroll
-    for (int c = 1; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[0][c]), s[0][c + 1 < 16 ? c + 1 : 0]);
-#pragma unroll
-    for (int c = 0; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[1][c]), s[1][c + 1]);
-    mx = half_max(mx);
-    if (__any(mx > m_run)) {
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int c = 0; c < 16; ++c) o_acc[db][c] *= alpha;
-      m_run = m_new;
-    }
-    const float msc = m_run == -INFINITY ? 0.f : m_run * sc;
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-#pragma unroll
-      for (int c = 0; c < 16; ++c) s[jb][c] = __builtin_amdgcn_exp2f(fmaf(s[jb][c], sc, -msc));
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 pb = pack8(s[jb], 8 * tt);
-        l_run = sum8(pb, l_run);
-        const char* vt = Vst + (jb * 32 + tt * 16) * 128;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-          o_acc[db] = mfma(read_transposed(vt, voff[db][0], voff[db][1]), pb, o_acc[db]);
-      }
-    }
+    fwd_tile(Kst, Vst, qf, koff, voff, sc, 0.f, CodeMask(code + t * BN, hl, me.code, me.global), o_acc, m_run, l_run);
   }
   __syncthreads();
   const float l_tot = half_sum(l_run);
@@ -282,34 +246,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_dense_kernel(DenseArgs a) {
     const char* Kst = stream.acquire(t, n_tiles);
     const char* Vst = Kst + kTileBytes;
     if (!wave_active) continue;
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-      f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        s = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s);     // S^T  = K Q^T
-        dp = mfma(read_plain(Vst + jb * 32 * 128, koff[ks]), gf[ks], dp);   // dP^T = V dO^T
-      }
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int4 kc = *reinterpret_cast<const int4*>(code + t * BN + jb * 32 + 8 * g + 4 * hl);
-        const int k4[4] = {kc.x, kc.y, kc.z, kc.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int c = 4 * g + r;
-          const float ds = __builtin_amdgcn_exp2f(fmaf(s[c], sc, -lse2)) * (dp[c] - delta);
-          s[c] = allowed(k4[r], me.code, me.global) ? ds : 0.f;
-        }
-      }
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 ds8 = pack8(s, 8 * tt);
-        const char* kt = Kst + (jb * 32 + tt * 16) * 128;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-          dq_acc[db] = mfma(read_transposed(kt, toff[db][0], toff[db][1]), ds8, dq_acc[db]);
-      }
-    }
+    dq_tile(Kst, Vst, qf, gf, koff, toff, sc, lse2, delta, CodeMask(code + t * BN, hl, me.code, me.global), dq_acc);
   }
   __syncthreads();
   const float mul = me.in_range && me.code > -2 ? a.scale : 0.f;  // pad positions: zeros
@@ -372,44 +309,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_dense_kernel(DenseArgs a) {
     const float* lse_row = reinterpret_cast<const float*>(Qst + kStage);
     const float* delta_row = lse_row + BN;
     if (!wave_active) continue;
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-      // accumulators start at the streamed queries' -lse / scale and -delta
-      f32x16 s, dp;
-      int qc[16];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int row0 = ib * 32 + 8 * g + 4 * hl;
-        const float4 l4 = *reinterpret_cast<const float4*>(lse_row + row0);
-        const float4 d4 = *reinterpret_cast<const float4*>(delta_row + row0);
-        const int4 c4 = *reinterpret_cast<const int4*>(code + t * BN + row0);
-        s[4 * g] = l4.x; s[4 * g + 1] = l4.y; s[4 * g + 2] = l4.z; s[4 * g + 3] = l4.w;
-        dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
-        qc[4 * g] = c4.x; qc[4 * g + 1] = c4.y; qc[4 * g + 2] = c4.z; qc[4 * g + 3] = c4.w;
-      }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        s = mfma(read_plain(Qst + ib * 32 * 128, poff[ks]), kf[ks], s);     // S  = Q K^T
-        dp = mfma(read_plain(Gst + ib * 32 * 128, poff[ks]), vf[ks], dp);   // dP = dO V^T
-      }
-#pragma unroll
-      for (int c = 0; c < 16; ++c) {
-        const float p = __builtin_amdgcn_exp2f(s[c] * sc);
-        s[c] = allowed(qc[c], me.code, me.global) ? p : 0.f;  // P
-        dp[c] *= s[c];                                        // dS
-      }
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 p8 = pack8(s, 8 * tt), ds8 = pack8(dp, 8 * tt);
-        const char* gt = Gst + (ib * 32 + tt * 16) * 128;
-        const char* qt = Qst + (ib * 32 + tt * 16) * 128;
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          dv_acc[db] = mfma(read_transposed(gt, toff[db][0], toff[db][1]), p8, dv_acc[db]);
-          dk_acc[db] = mfma(read_transposed(qt, toff[db][0], toff[db][1]), ds8, dk_acc[db]);
-        }
-      }
-    }
+    dkv_tile(Qst, Gst, lse_row, delta_row, kf, vf, poff, toff, sc, hl, CodeMask(code + t * BN, hl, me.code, me.global), dk_acc, dv_acc);
   }
   __syncthreads();
   const bool live = me.in_range && me.code > -2;  // pad positions: zeros

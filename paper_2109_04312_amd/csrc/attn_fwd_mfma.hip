@@ -19,6 +19,7 @@
 #include "launch.h"
 #include "mfma_common.h"
 #include "stream_plan.h"
+#include "tile_bodies.h"
 #include "tile_stream.h"
 
 namespace mate {
@@ -90,13 +91,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
   asm volatile("" ::"v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]));
 
   int koff[4], voff[2][2];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) koff[ks] = plain_off(m, hl, ks);
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
-    voff[db][0] = tr_off(lane, db, 0);
-    voff[db][1] = tr_off(lane, db, 1);
-  }
+  operand_offsets(lane, koff, voff);
 
   for (int t = tb; t < te; ++t) {
     const char* Kst = stream.acquire(t);
@@ -107,62 +102,8 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
     const int base = part0 ? t * BN : u.s_lo + (t - u.n_t0) * BN;
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
-      // S^T = K Q^T : rows = keys of the tile, columns = this wave's queries
-      f32x16 s[2] = {zero16(), zero16()};
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          s[jb] = mfma(read_plain(Kst + jb * 32 * 128, koff[ks]), qf[ks], s[jb]);
-
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      if (!full) {  // wave-uniform: some (query, key) pairs of this tile are outside the pattern
-        const int lo = part0 ? 0 : me.lo, hi = part0 ? u.G : me.hi;
-        const int d0 = base + 4 * hl - lo;
-        const unsigned len = (unsigned)(hi - lo);
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-          for (int c = 0; c < 16; ++c) {
-            const bool in = (unsigned)(d0 + jb * 32 + 8 * (c >> 2) + (c & 3)) < len;
-            s[jb][c] = in ? s[jb][c] : -INFINITY;
-          }
-      }
-      float mx = s[0][0];
-#pragma unroll
-      for (int c = 1; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[0][c]), s[0][c + 1 < 16 ? c + 1 : 0]);
-#pragma unroll
-      for (int c = 0; c < 16; c += 2) mx = fmaxf(fmaxf(mx, s[1][c]), s[1][c + 1]);
-      mx = half_max(mx);
-      // Rescale only when some row's maximum has moved up by more than 2^kLazyBits in the exponent
-      // domain.  Until then probabilities may exceed 1 by that factor, which changes neither
-      // their relative rounding in bf16 nor the fp32 sums' accuracy.
-      if (__any(mx > m_run + lazy)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int c = 0; c < 16; ++c) o_acc[db][c] *= alpha;
-        m_run = m_new;
-      }
-      const float msc = m_run == -INFINITY ? 0.f : m_run * sc;
-      // P^T = exp2(S^T sc - m sc), rounded to bf16;  O^T += V^T P^T;  l += sum of rounded P
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-#pragma unroll
-        for (int c = 0; c < 16; ++c) s[jb][c] = __builtin_amdgcn_exp2f(fmaf(s[jb][c], sc, -msc));
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 pb = pack8(s[jb], 8 * tt);
-          l_run = sum8(pb, l_run);
-          const char* vt = Vst + (jb * 32 + tt * 16) * 128;
-#pragma unroll
-          for (int db = 0; db < 2; ++db)
-            o_acc[db] = mfma(read_transposed(vt, voff[db][0], voff[db][1]), pb, o_acc[db]);
-        }
-      }
+      fwd_tile(Kst, Vst, qf, koff, voff, sc, lazy, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), o_acc, m_run, l_run);
     }
     stream.release();
   }
