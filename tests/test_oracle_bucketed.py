@@ -92,55 +92,46 @@ def test_pair_count_closed_form_single_segment(n_tok, radius):
         assert want == (3 * (n_tok // radius) - 2) * radius * radius
 
 
-# ---- the computation of the appendix, with views instead of a mask -------------------------
-def views_forward(q, k, v, ids, flags, g_len, radius, scale):
-    """One (sequence, head).  Returns O [N, D] (zeros at pads)."""
+# ---- Section 3.1 read as prose, token by token (no mask matrix) ----------------------------
+def prose_forward(q, k, v, ids, flags, g_len, radius, scale):
+    """One (sequence, head), written from the section's description alone: the input is ordered
+    by the head's traversal; its first g_len question tokens form the global part, which attends
+    to everything; the rest is cut into buckets of `radius` consecutive tokens of that order; a
+    token of bucket j attends to the global part and to those tokens of buckets j - 1, j, j + 1
+    that share its row / column.  Plain loops over buckets and tokens with explicit key lists and
+    a softmax by hand.  Returns O [N, D] (zeros at pads)."""
+    import math
     N, D = q.shape
-    quest = [p for p in range(N) if flags[p] == G]
-    glob, extra = quest[:g_len], quest[g_len:]
-    table = sorted([p for p in range(N) if flags[p] == L] + extra, key=lambda p: (int(ids[p]), p))
-    full = glob + table                                  # every non-pad token
-    n_b = -(-len(table) // radius) if table else 0
+    question = [p for p in range(N) if flags[p] == G]
+    global_part = question[:g_len]
+    rest = [p for p in range(N) if flags[p] == L] + question[g_len:]
+    rest.sort(key=lambda p: (int(ids[p]), p))                 # the head's order of traversal
+    buckets = [rest[s:s + radius] for s in range(0, len(rest), radius)]
     out = np.zeros((N, D))
 
-    def softmax(x):
-        with np.errstate(invalid="ignore"):     # filler rows of the last bucket have no keys
-            e = np.exp(x - x.max(axis=-1, keepdims=True))
-            return e / e.sum(axis=-1, keepdims=True)
+    def attend(query, keys):
+        scores = [scale * sum(q[query, d] * k[j, d] for d in range(D)) for j in keys]
+        top = max(scores)
+        weights = [math.exp(x - top) for x in scores]
+        total = sum(weights)
+        for j, wgt in zip(keys, weights):
+            for d in range(D):
+                out[query, d] += wgt / total * v[j, d]
 
-    if glob:                                             # global rows see the full sequence
-        pg = softmax(scale * np.einsum("fe,te->ft", q[glob], k[full]))
-        out[glob] = np.einsum("ft,te->fe", pg, v[full])
-    if not table:
-        return out
-    # long view [n_b, R]: token position per bucket entry, -1 = filler of the last bucket
-    long_tok = np.full(n_b * radius, -1, np.int64)
-    long_tok[:len(table)] = table
-    long_tok = long_tok.reshape(n_b, radius)
-    filler_row = np.full((1, radius), -1, np.int64)
-    prev_tok = np.concatenate([filler_row, long_tok[:-1]], axis=0)   # bucket j - 1 (none for j = 0)
-    next_tok = np.concatenate([long_tok[1:], filler_row], axis=0)    # bucket j + 1 (none for the last)
-    window_tok = np.concatenate([prev_tok, long_tok, next_tok], axis=1)     # [n_b, 3R]
-    take = lambda x, tok: np.where((tok >= 0)[..., None], x[np.maximum(tok, 0)], 0.0)
-    id_of = lambda tok: np.where(tok >= 0, np.asarray(ids, np.int64)[np.maximum(tok, 0)], -1)
-    q_long, k_win, v_win = take(q, long_tok), take(k, window_tok), take(v, window_tok)
-    to_global = scale * np.einsum("nfe,te->nft", q_long, k[glob]) if glob else np.zeros((n_b, radius, 0))
-    to_window = scale * np.einsum("nfe,nte->nft", q_long, k_win)
-    # the part the listing leaves out: no attention across rows / columns, none to fillers
-    ok = (id_of(long_tok)[:, :, None] == id_of(window_tok)[:, None, :]) & (window_tok >= 0)[:, None, :]
-    to_window = np.where(ok, to_window, -np.inf)
-    prob = softmax(np.concatenate([to_global, to_window], axis=-1))
-    p_g, p_w = prob[..., :len(glob)], prob[..., len(glob):]
-    ctx = np.einsum("nft,nte->nfe", p_w, v_win)
-    if glob:
-        ctx = ctx + np.einsum("nft,te->nfe", p_g, v[glob])
-    valid = long_tok >= 0
-    out[long_tok[valid]] = ctx[valid]
+    for query in global_part:
+        attend(query, global_part + rest)
+    for j, bucket in enumerate(buckets):
+        nearby = []
+        for jj in (j - 1, j, j + 1):
+            if 0 <= jj < len(buckets):
+                nearby += buckets[jj]
+        for query in bucket:
+            attend(query, global_part + [t for t in nearby if ids[t] == ids[query]])
     return out
 
 
 @pytest.mark.parametrize("seed", range(5))
-def test_forward_equals_the_computation_with_views(seed):
+def test_forward_equals_the_section_read_token_by_token(seed):
     rng = np.random.default_rng(100 + seed)
     N, D = 70, 5
     st = synth.random_structure(rng, 3, N, max_rows=5, max_cols=4, max_global=8, max_cell=6,
@@ -151,7 +142,7 @@ def test_forward_equals_the_computation_with_views(seed):
         o, _ = orc.attn_forward(q, k, v, st.row_ids, st.col_ids, st.flags, hk, 0.7, bucketed=(g_len, radius))
         for b in range(3):
             for h, ids in ((0, st.row_ids[b]), (1, st.col_ids[b])):
-                want = views_forward(q[b, h], k[b, h], v[b, h], ids, st.flags[b], g_len, radius, 0.7)
+                want = prose_forward(q[b, h], k[b, h], v[b, h], ids, st.flags[b], g_len, radius, 0.7)
                 assert np.abs(o[b, h] - want).max() < 1e-12, (g_len, radius, b, h)
 
 
