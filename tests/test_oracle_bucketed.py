@@ -3,11 +3,11 @@
 What the paper fixes, and what is checked against it here:
   * the claim at the end of Section 3.1: once G holds the question part and R holds the longest
     row / column, the bucketed pattern IS the mask-based pattern of Section 3;
-  * the computation the appendix describes (a `global` view, a `long` view of buckets of R, a
-    `window` view of each bucket with its two neighbours; scores from the global rows to the
-    full sequence, from the long rows to the global part and to their window; one softmax over
-    the concatenation of the latter two; contexts added), written out below with reshapes and
-    shifted copies instead of a mask, must give the oracle's outputs;
+  * the section's own description read token by token (the first G question tokens attend to
+    and from everything; the rest of the head's order is cut into buckets of R; a token of
+    bucket j attends to the global part and to the tokens of buckets j - 1, j, j + 1 that share
+    its row / column), written out below as plain loops with explicit key lists and a softmax
+    by hand, must give the oracle's outputs;
   * a hand-derived 8-token example and closed-form pair counts.
 The readings the paper leaves open (how the global part is filled, no wrap-around between the
 first and the last bucket) are shared by both sides of these tests: for them parity is
