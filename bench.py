@@ -76,7 +76,8 @@ def summarize_pmc(fetch_dir, write_dir):
         for path in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
             for row in csv.DictReader(open(path)):
                 if row["Counter_Name"] == counter:
-                    name = row["Kernel_Name"].split("(")[0].replace("void mate::(anonymous namespace)::", "")
+                    name = row["Kernel_Name"].replace("(anonymous namespace)::", "").replace("void ", "")
+                    name = name.split("(")[0].replace("mate::", "")
                     acc.setdefault(name, {}).setdefault(row["Dispatch_Id"], 0.0)
                     acc[name][row["Dispatch_Id"]] += float(row["Counter_Value"])
         return {k: sum(v.values()) / len(v) for k, v in acc.items()}
@@ -84,7 +85,7 @@ def summarize_pmc(fetch_dir, write_dir):
     fetch, write = per_kernel(fetch_dir, "FETCH_SIZE"), per_kernel(write_dir, "WRITE_SIZE")
     print("sources", sources_digest())
     for k in sorted(fetch):
-        if "mate" in k or "kernel" in k:
+        if k.endswith("_kernel") or "_kernel<" in k:
             print("counter", k.replace(" ", ""), round(fetch[k]), round(write.get(k, 0.0)))
 
 
@@ -302,6 +303,9 @@ def main():
     ap.add_argument("--bucketed", default=None, metavar="G,R",
                     help="bucketed mode of Section 3.1 (the published models use 116,42)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain", action="store_true",
+                    help="for profiler runs: only the warm-up and the timed steps of the chosen configuration "
+                         "(no per-kernel event pass, no per-head-kind runs, no peak probes, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy three times (to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
@@ -385,6 +389,11 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     block_ms = sorted(marks[i].elapsed_time(marks[i + 1]) / block for i in range(len(marks) - 1))
     ms_median, ms_min = block_ms[len(block_ms) // 2], block_ms[0]
+
+    if args.plain:
+        print(json.dumps({"plain": True, "workload": w.name, "steps": args.steps, "ms_per_step": ms_per_step,
+                          "ms_per_step_median": ms_median, "ms_per_step_min": ms_min}))
+        return
 
     # second pass of the same loop: HIP events recorded by the library around ONE kernel launch
     # per step (on the stream the kernels run on), cycling through the kernels

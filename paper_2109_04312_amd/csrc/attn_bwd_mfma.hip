@@ -112,7 +112,7 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      dq_tile(Kst, Vst, qf, gf, koff, toff, sc, lse2, delta, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), dq_acc);
+      dq_tile(Kst, Vst, qf, gf, koff, toff, sc, lse2, delta, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi, part0 ? 0 : me.w_lo, part0 ? u.G : me.w_hi), dq_acc);
     }
     stream.release();
   }
@@ -205,7 +205,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      dkv_tile(Qst, Gst, lse_row, delta_row, kf, vf, poff, toff, sc, hl, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), dk_acc, dv_acc);
+      dkv_tile(Qst, Gst, lse_row, delta_row, kf, vf, poff, toff, sc, hl, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi, part0 ? 0 : me.w_lo, part0 ? u.G : me.w_hi), dk_acc, dv_acc);
     }
     stream.release();
   }

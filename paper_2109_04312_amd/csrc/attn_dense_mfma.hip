@@ -125,6 +125,7 @@ struct CodeMask {
       k[4 * g] = kc.x; k[4 * g + 1] = kc.y; k[4 * g + 2] = kc.z; k[4 * g + 3] = kc.w;
     }
   }
+  __device__ __forceinline__ bool skip(int) const { return false; }
   __device__ __forceinline__ bool in(int, int c) const { return allowed(k[c], my_code, my_global); }
 };
 

@@ -103,7 +103,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
     const bool skip = !me.wave_active || (!part0 && (base >= me.w_hi || base + BN <= me.w_lo));
     if (!skip) {
       const bool full = part0 ? (base + BN <= u.G) : (base >= me.a_lo && base + BN <= me.a_hi);
-      fwd_tile(Kst, Vst, qf, koff, voff, sc, lazy, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi), o_acc, m_run, l_run);
+      fwd_tile(Kst, Vst, qf, koff, voff, sc, lazy, WindowMask(full, base, hl, part0 ? 0 : me.lo, part0 ? u.G : me.hi, part0 ? 0 : me.w_lo, part0 ? u.G : me.w_hi), o_acc, m_run, l_run);
     }
     stream.release();
   }

@@ -4,6 +4,7 @@
 // streamed row) pairs belong to the attention pattern differs.  That rule is the Mask argument:
 //
 //   mask.full          wave-uniform: every pair of this tile belongs to the pattern (no masking)
+//   mask.skip(blk)     wave-uniform: no pair of the 32-row block blk belongs to the pattern
 //   mask.load(blk)     fetch what in() needs for the 32-row block blk of the tile
 //   mask.in(blk, c)    does the pair (this lane's owned row, streamed row c_row(c) of block blk)
 //                      belong to the pattern?  c = accumulator register 0..15
@@ -37,8 +38,13 @@ struct WindowMask {
   const bool full;
   const int d0;        // base + 4 hl - lo
   const unsigned len;  // hi - lo
-  __device__ __forceinline__ WindowMask(bool full_, int base, int hl, int lo, int hi)
-      : full(full_), d0(base + 4 * hl - lo), len((unsigned)(hi - lo)) {}
+  const int skip_lo, skip_hi;  // wave-uniform: block blk is outside every row's window iff
+                               // 32 blk >= skip_hi or 32 blk + 32 <= skip_lo
+  // [u_lo, u_hi) = union of the windows of the wavefront's rows, in the same slot numbering as base
+  __device__ __forceinline__ WindowMask(bool full_, int base, int hl, int lo, int hi, int u_lo, int u_hi)
+      : full(full_), d0(base + 4 * hl - lo), len((unsigned)(hi - lo)), skip_lo(u_lo - base),
+        skip_hi(u_hi - base) {}
+  __device__ __forceinline__ bool skip(int blk) const { return 32 * blk >= skip_hi || 32 * blk + 32 <= skip_lo; }
   __device__ __forceinline__ void load(int) const {}
   __device__ __forceinline__ bool in(int blk, int c) const {
     return (unsigned)(d0 + blk * 32 + 8 * (c >> 2) + (c & 3)) < len;
@@ -53,7 +59,9 @@ __device__ __forceinline__ void fwd_tile(const char* Kst, const char* Vst, const
                                          const int (&koff)[4], const int (&voff)[2][2], float sc,
                                          float lazy, Mask&& mask, f32x16 (&o_acc)[2], float& m_run,
                                          float& l_run) {
-  // S^T = K Q^T : rows = keys of the tile, columns = this wave's queries
+  // S^T = K Q^T : rows = keys of the tile, columns = this wave's queries.  (Both 32-key blocks
+  // are always computed here: skipping invisible blocks, as the backward bodies do, made this
+  // one slower -- the two blocks' instruction streams no longer interleave.)
   f32x16 s[2] = {zero16(), zero16()};
 #pragma unroll
   for (int jb = 0; jb < 2; ++jb)
@@ -114,6 +122,7 @@ __device__ __forceinline__ void dq_tile(const char* Kst, const char* Vst, const 
                                         Mask&& mask, f32x16 (&dq_acc)[2]) {
 #pragma unroll
   for (int jb = 0; jb < 2; ++jb) {
+    if (mask.skip(jb)) continue;
     f32x16 s = zero16(), dp = zero16();
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -151,6 +160,7 @@ __device__ __forceinline__ void dkv_tile(const char* Qst, const char* Gst, const
                                          f32x16 (&dk_acc)[2], f32x16 (&dv_acc)[2]) {
 #pragma unroll
   for (int ib = 0; ib < 2; ++ib) {
+    if (mask.skip(ib)) continue;
     f32x16 s, dp;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
