@@ -304,8 +304,9 @@ def main():
                     help="bucketed mode of Section 3.1 (the published models use 116,42)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true",
-                    help="for profiler runs: only the warm-up and the timed steps of the chosen configuration "
-                         "(no per-kernel event pass, no per-head-kind runs, no peak probes, no CPU baseline)")
+                    help="for profiler runs: the warm-up, the timed steps and the per-kernel event pass of the "
+                         "chosen configuration, every launch the same shape (no per-head-kind runs, no peak "
+                         "probes, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy three times (to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
@@ -390,11 +391,6 @@ def main():
     block_ms = sorted(marks[i].elapsed_time(marks[i + 1]) / block for i in range(len(marks) - 1))
     ms_median, ms_min = block_ms[len(block_ms) // 2], block_ms[0]
 
-    if args.plain:
-        print(json.dumps({"plain": True, "workload": w.name, "steps": args.steps, "ms_per_step": ms_per_step,
-                          "ms_per_step_median": ms_median, "ms_per_step_min": ms_min}))
-        return
-
     # second pass of the same loop: HIP events recorded by the library around ONE kernel launch
     # per step (on the stream the kernels run on), cycling through the kernels
     import ctypes as C
@@ -426,6 +422,13 @@ def main():
         kernel_s[name] = sum(samples) / len(samples)
         kernel_median_s[name] = samples[len(samples) // 2]
         kernel_min_s[name] = samples[0]
+    if args.plain:
+        print(json.dumps({"plain": True, "workload": w.name, "steps": args.steps, "ms_per_step": ms_per_step,
+                          "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+                          "kernel_us_hip_events": {n: {"avg": 1e6 * kernel_s[n], "median": 1e6 * kernel_median_s[n],
+                                                       "min": 1e6 * kernel_min_s[n], "launches": per_kernel}
+                                                   for n in kernels}}))
+        return
     t_build, t_fwd = kernel_s["build_segments"], kernel_s["attn_fwd"]
     t_dq, t_dkv = kernel_s["attn_bwd_dq"], kernel_s["attn_bwd_dkv"]
 

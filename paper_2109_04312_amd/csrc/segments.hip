@@ -153,8 +153,10 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
   static_assert(P2 * sizeof(unsigned short) >= kBins * sizeof(int), "histograms must fit the order buffers");
 
   const int b = blockIdx.x, view = blockIdx.y, tid = threadIdx.x;
-  const int k = blockIdx.z, K = gridDim.z;   // this workgroup's share of the (sequence, view)
-  const int chunk = (((N + K - 1) / K) + 63) & ~63, c0 = k * chunk, c1 = min(N, c0 + chunk);
+  // Several workgroups per (sequence, view): K of them take a chunk of the positions each, one
+  // more (k == K, no chunk) lists the work units.
+  const int k = blockIdx.z, K = gridDim.z > 1 ? (int)gridDim.z - 1 : 1;
+  const int chunk = (((N + K - 1) / K) + 63) & ~63, c0 = k < K ? k * chunk : 0, c1 = min(N, c0 + chunk);
   const int lane = tid & 63, wave = tid >> 6;
   const SegLayout lay(B, N);
   int* counts = seg + lay.counts + (size_t)b * kCountWords;
@@ -320,6 +322,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
     };
 
     // ---- this workgroup's chunk of positions: rank among equal ids, kind lists ----------------
+    if (k < K) {
     int code[NBC], rank_w[NBC], g_rank[NBC], p_rank[NBC];
     int g_w = 0, p_w = 0;
 #pragma unroll
@@ -379,6 +382,7 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
         slot_rng[p] = p < L ? window(p) : make_int2(0, 0);
       }
     }
+    }
     // ---- per-sequence and per-segment tables (first workgroup) -----------------------------------
     if (k == 0) {
       if (tid < (int)kBins && c_id > 0) seg_off[seg_index] = first_slot;
@@ -389,8 +393,8 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
         if (view == 0) { counts[C_G] = G; counts[C_L] = L; counts[C_P] = P; }
       }
     }
-    if (k != K - 1) return;
-    // ---- work units of the attention kernels (last workgroup) ------------------------------------
+    if (k != K) return;
+    // ---- work units of the attention kernels (the workgroup without a chunk) ---------------------
     // A run is a segment of at least kBigSegment slots, or the shorter segments between two such
     // segments; units are 128-slot pieces of runs (see the general path below for why).
     const int* sstart = seg_tmp[0];
@@ -718,8 +722,10 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
 hipError_t launch_build_segments(const int* row_ids, const int* col_ids,
                                  const unsigned char* flags, int B, int N, int max_global,
                                  int radius, int* seg, hipStream_t stream) {
-  // up to eight workgroups per (sequence, view), at least 1024 positions each
-  dim3 grid(B, 2, std::min(8, (N + kSegThreads - 1) / kSegThreads)), block(kSegThreads);
+  // up to eight workgroups per (sequence, view) with at least 1024 positions each, and with more
+  // than one of them a further one for the work-unit list
+  const int chunks = std::min(8, (N + kSegThreads - 1) / kSegThreads);
+  dim3 grid(B, 2, chunks > 1 ? chunks + 1 : 1), block(kSegThreads);
   ProfileScope prof(1, stream);
 #define MATE_SEG_CASE(P2)                                                                  \
   if (N <= P2) {                                                                            \
