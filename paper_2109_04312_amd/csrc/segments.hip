@@ -9,7 +9,9 @@
 //     everything else (segments, windows, work units) follows from the histogram of ids.  Up to
 //     eight workgroups share a (sequence, view): each reads the whole sequence (a few KB),
 //     builds the histogram and the part of it that lies before its own chunk of positions, and
-//     ranks and writes only its chunk.  Nothing is exchanged between workgroups.
+//     ranks and writes only its chunk; one more workgroup has no chunk and lists the work units
+//     instead (the longest single piece of work after the histogram).  Nothing is exchanged
+//     between workgroups.
 //   * otherwise (short sequences, where one workgroup is as fast; large ids): workgroup 0 of the
 //     (sequence, view) sorts alone, as described next.
 //
@@ -323,65 +325,65 @@ __global__ __launch_bounds__(kSegThreads) void build_segments_kernel(
 
     // ---- this workgroup's chunk of positions: rank among equal ids, kind lists ----------------
     if (k < K) {
-    int code[NBC], rank_w[NBC], g_rank[NBC], p_rank[NBC];
-    int g_w = 0, p_w = 0;
+      int code[NBC], rank_w[NBC], g_rank[NBC], p_rank[NBC];
+      int g_w = 0, p_w = 0;
 #pragma unroll
-    for (int j = 0; j < NBC; ++j) {
-      const int p = c0 + (wave * NBC + j) * 64 + lane;
-      code[j] = p < c1 ? ids[p] : -3;
-      const bool local = code[j] >= 0;
-      const unsigned dg = local ? (unsigned)code[j] : 0u;
-      const unsigned long long same = match_digit(dg, local, varying_bits(dg, local));
-      const int before = lanes_before(same);
-      int old = 0;
-      if (local && before == 0) {  // first lane of a group of equal ids
-        old = hist[wave][dg];
-        hist[wave][dg] = (unsigned short)(old + __popcll(same));
-      }
-      old = __shfl(old, local ? __ffsll((long long)same) - 1 : lane, 64);
-      rank_w[j] = old + before;
-      const unsigned long long mg = __ballot(code[j] == -1), mp = __ballot(code[j] == -2);
-      g_rank[j] = g_w + lanes_before(mg);
-      p_rank[j] = p_w + lanes_before(mp);
-      g_w += __popcll(mg);
-      p_w += __popcll(mp);
-    }
-    if (lane == 0) { wave_tot[1][wave] = g_w; wave_tot[2][wave] = p_w; }
-    lds_barrier();
-    // (id, wavefront) counts -> tokens with that id before the wavefront's block
-    if (tid < (int)kBins) {
-      int running = before_h[tid];
-#pragma unroll
-      for (int w = 0; w < kSegWaves; ++w) {
-        const int c = hist[w][tid];
-        hist[w][tid] = (unsigned short)running;
-        running += c;
-      }
-    }
-    int g_at_c = g_before, p_at_c = p_before;
-#pragma unroll
-    for (int w = 0; w < kSegWaves; ++w)
-      if (w < wave) { g_at_c += wave_tot[1][w]; p_at_c += wave_tot[2][w]; }
-    lds_barrier();
-#pragma unroll
-    for (int j = 0; j < NBC; ++j) {
-      const int p = c0 + (wave * NBC + j) * 64 + lane;
-      if (p < c1) {
-        if (code[j] >= 0) {
-          const int slot = start_v[code[j]] + hist[wave][code[j]] + rank_w[j];
-          perm[slot] = p;
-          seg_of_tok[p] = seg_i[code[j]];
-        } else {
-          seg_of_tok[p] = -1;
-          if (view == 0) {
-            if (code[j] == -1) global_idx[g_at_c + g_rank[j]] = p;
-            else pad_idx[p_at_c + p_rank[j]] = p;
-          }
+      for (int j = 0; j < NBC; ++j) {
+        const int p = c0 + (wave * NBC + j) * 64 + lane;
+        code[j] = p < c1 ? ids[p] : -3;
+        const bool local = code[j] >= 0;
+        const unsigned dg = local ? (unsigned)code[j] : 0u;
+        const unsigned long long same = match_digit(dg, local, varying_bits(dg, local));
+        const int before = lanes_before(same);
+        int old = 0;
+        if (local && before == 0) {  // first lane of a group of equal ids
+          old = hist[wave][dg];
+          hist[wave][dg] = (unsigned short)(old + __popcll(same));
         }
-        // the same index range, read as sorted slots: their windows
-        slot_rng[p] = p < L ? window(p) : make_int2(0, 0);
+        old = __shfl(old, local ? __ffsll((long long)same) - 1 : lane, 64);
+        rank_w[j] = old + before;
+        const unsigned long long mg = __ballot(code[j] == -1), mp = __ballot(code[j] == -2);
+        g_rank[j] = g_w + lanes_before(mg);
+        p_rank[j] = p_w + lanes_before(mp);
+        g_w += __popcll(mg);
+        p_w += __popcll(mp);
       }
-    }
+      if (lane == 0) { wave_tot[1][wave] = g_w; wave_tot[2][wave] = p_w; }
+      lds_barrier();
+      // (id, wavefront) counts -> tokens with that id before the wavefront's block
+      if (tid < (int)kBins) {
+        int running = before_h[tid];
+#pragma unroll
+        for (int w = 0; w < kSegWaves; ++w) {
+          const int c = hist[w][tid];
+          hist[w][tid] = (unsigned short)running;
+          running += c;
+        }
+      }
+      int g_at_c = g_before, p_at_c = p_before;
+#pragma unroll
+      for (int w = 0; w < kSegWaves; ++w)
+        if (w < wave) { g_at_c += wave_tot[1][w]; p_at_c += wave_tot[2][w]; }
+      lds_barrier();
+#pragma unroll
+      for (int j = 0; j < NBC; ++j) {
+        const int p = c0 + (wave * NBC + j) * 64 + lane;
+        if (p < c1) {
+          if (code[j] >= 0) {
+            const int slot = start_v[code[j]] + hist[wave][code[j]] + rank_w[j];
+            perm[slot] = p;
+            seg_of_tok[p] = seg_i[code[j]];
+          } else {
+            seg_of_tok[p] = -1;
+            if (view == 0) {
+              if (code[j] == -1) global_idx[g_at_c + g_rank[j]] = p;
+              else pad_idx[p_at_c + p_rank[j]] = p;
+            }
+          }
+          // the same index range, read as sorted slots: their windows
+          slot_rng[p] = p < L ? window(p) : make_int2(0, 0);
+        }
+      }
     }
     // ---- per-sequence and per-segment tables (first workgroup) -----------------------------------
     if (k == 0) {
