@@ -179,6 +179,31 @@ def test_backward_is_bit_reproducible():
     assert torch.equal(out, out2) and torch.equal(lse, lse2)
 
 
+@pytest.mark.parametrize("id_step", [1, 1000])
+def test_more_unit_cuts_than_records(id_step):
+    """Every row is a segment of 129 slots and every column one of 258: cutting at each of them
+    would need about twice as many unit records as a view has, so the builder falls back to a cut
+    every 128 slots, and units straddle long segments again.  id_step = 1000 takes the ids past
+    the counting sort's range (general sorting path)."""
+    N, rows, cols = 4096, 30, 15
+    L, G, P = synth.TOK_LOCAL, synth.TOK_GLOBAL, synth.TOK_PAD
+    flags = np.full((1, N), P, np.uint8)
+    row = np.zeros((1, N), np.int32)
+    col = np.zeros((1, N), np.int32)
+    flags[0, :20] = G
+    n = rows * 129
+    assert n == cols * 258 and 20 + n <= N
+    flags[0, 20:20 + n] = L
+    i = np.arange(n)
+    row[0, 20:20 + n] = (1 + i // 129) * id_step
+    col[0, 20:20 + n] = (1 + i % cols) * id_step
+    st = synth.Structure(row, col, flags)
+    rng = np.random.default_rng(129 + id_step)
+    q, k, v, do = synth.draw_tensors(rng, 1, 2, N, 64, "bf16", 4)
+    w = synth.Workload(f"cuts_step{id_step}", "bf16", st, np.array([ROW, COL], np.uint8), q, k, v, do, 0.125)
+    check_workload(w, backward=True)
+
+
 def test_head_kind_mix_and_order():
     # any assignment of kinds to heads, not only "first half rows"
     w = small_workload(8, "bf16", B=1, N=260, H=5, max_rows=10, max_cols=5, max_global=9)

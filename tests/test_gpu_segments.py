@@ -66,6 +66,25 @@ def test_segments_bad_ids_reported():
     assert e.value.status == mate.MATE_ERR_BAD_ID
 
 
+def test_segments_many_sequences():
+    """More sequences than the export and status calls copy per batch (64): tables of every
+    sequence bit-exact, and an invalid id in a late sequence still reported."""
+    from paper_2109_04312_amd import mate
+    B, N = 150, 48
+    rng = np.random.default_rng(150)
+    st = synth.random_structure(rng, B, N, max_rows=6, max_cols=4, max_global=8, max_cell=3,
+                                scatter=True, sparse_ids=False)
+    seg = _build(st)
+    hp.compare_segments(seg, st)
+    assert mate.segments_status(seg) == mate.MATE_OK
+    row = st.row_ids.copy()
+    b = max(i for i in range(128, B) if (st.flags[i] == synth.TOK_LOCAL).any())
+    k = int(np.nonzero(st.flags[b] == synth.TOK_LOCAL)[0][0])
+    row[b, k] = -1
+    seg = _build(synth.Structure(row, st.col_ids, st.flags))
+    assert mate.segments_status(seg) == mate.MATE_ERR_BAD_ID
+
+
 def test_segments_rebuild_is_deterministic_and_reusable():
     """The builder writes the valid part of every list only, so determinism is checked on
     zero-filled buffers, and reuse in place (stale entries of another batch behind the valid
