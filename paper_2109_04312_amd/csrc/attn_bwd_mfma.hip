@@ -132,7 +132,7 @@ __device__ __forceinline__ void bwd_dq_unit(const AttnArgs& a, const Work& w) {
 // fit at once and the stragglers double the kernel's critical path)
 __global__ __launch_bounds__(kThreads, 4) void bwd_dq_mfma_kernel(AttnArgs a) {
   Work w;
-  if (!take_unit(a, w)) return;
+  if (!take_unit<true>(a, w)) return;
   bwd_dq_unit(a, w);
 }
 
@@ -224,7 +224,7 @@ __device__ __forceinline__ void bwd_dkv_unit(const AttnArgs& a, const Work& w) {
 
 __global__ __launch_bounds__(kThreads) void bwd_dkv_mfma_kernel(AttnArgs a) {
   Work w;
-  if (!take_unit(a, w)) return;
+  if (!take_unit<true>(a, w)) return;
   bwd_dkv_unit(a, w);
 }
 

@@ -128,7 +128,7 @@ __device__ __forceinline__ void fwd_unit(const AttnArgs& a, const Work& w) {
 
 __global__ __launch_bounds__(kThreads, 4) void fwd_mfma_kernel(AttnArgs a) {
   Work w;
-  if (!take_unit(a, w)) return;
+  if (!take_unit<false>(a, w)) return;
   fwd_unit(a, w);
 }
 

@@ -23,6 +23,12 @@
 //      real ones unless a sequence has more than 128 question tokens)
 //   3. row heads, as in 1
 //   4. what is left of the three lists (real records only in the cases named above)
+// The two backward kernels run 2 before 1: there the question-token chunks are as long as the
+// column-head units, and more of both exist than workgroup slots, so whichever kind comes second
+// has members that start late and end last; the chunks first measured 1-6 us better on four of
+// the five benchmark shapes and the same on the fifth.  In the forward the empty records at the
+// end of 2 (a sequence with few chunks) would then sit in front of every column-head unit, which
+// cost more than the order won.
 // Records of kind "none" pad every pair to the same count; their workgroups exit at once.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -69,6 +75,7 @@ __device__ inline int head_at(const AttnArgs& a, int i) {
 
 // Returns false if this workgroup has nothing to do.  Everything here is wave-uniform and
 // stays in scalar registers.
+template <bool kChunksFirst>
 __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   const int T = a.seg.tiles, U = a.seg.units, N = a.N, n_col = a.n_col, n_row = a.H - n_col;
   const int q = blockIdx.x & 7;
@@ -85,13 +92,15 @@ __device__ inline bool take_unit(const AttnArgs& a, Work& w) {
   const int E = min(U, T), T1 = min(T, (T >> 3) + 2);
   int t = blockIdx.x >> 3;
   // region -> (first pair, pairs, first record, records per pair)
-  int first = 0, pairs = nc, k0 = 0, per = E;
-  bool glob = false;
   const int n_all = nc + nr;
-  if (t >= nc * E) {                       // question-token owners, early part
-    t -= nc * E; first = 0; pairs = n_all; k0 = 0; per = T1; glob = true;
-    if (t >= n_all * T1) {                 // row heads, early part
-      t -= n_all * T1; first = nc; pairs = nr; k0 = 0; per = E; glob = false;
+  // the first two regions: column heads then question-token owners (early parts), or the reverse
+  const int len_a = kChunksFirst ? n_all * T1 : nc * E, len_b = kChunksFirst ? nc * E : n_all * T1;
+  bool glob = kChunksFirst;
+  int first = 0, pairs = glob ? n_all : nc, k0 = 0, per = glob ? T1 : E;
+  if (t >= len_a) {
+    t -= len_a; glob = !kChunksFirst; pairs = glob ? n_all : nc; per = glob ? T1 : E;
+    if (t >= len_b) {                      // row heads, early part
+      t -= len_b; first = nc; pairs = nr; k0 = 0; per = E; glob = false;
       if (t >= nr * E) {                   // column heads, rest
         t -= nr * E; first = 0; pairs = nc; k0 = E; per = U - E;
         if (t >= nc * (U - E)) {           // row heads, rest
