@@ -448,10 +448,7 @@ def main():
     if args.plain:
         print(json.dumps({"plain": True, "workload": w.name, "steps": args.steps, "settle_steps": settle_steps,
                           "ms_per_step": ms_per_step,
-                          "untimed_before_warmup": {"settle_s": args.settle_s, "steps": settle_steps,
-                                  "why": "the same step repeated until the clocks have settled, so that a short "
-                                         "run reads like a long one; not part of the timed region"},
-        "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+                          "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
                           "kernel_us_hip_events": {n: {"avg": 1e6 * kernel_s[n], "median": 1e6 * kernel_median_s[n],
                                                        "min": 1e6 * kernel_min_s[n], "launches": per_kernel}
                                                    for n in kernels}}))
@@ -580,6 +577,9 @@ def main():
                    "col_heads": int((hk == 1).sum()), "non_pad_tokens": nonpad, "useful_pairs": pairs,
                    "step": ("mate_build_segments_bucketed" if bucketed else "mate_build_segments")
                            + " + mate_attn_fwd + mate_attn_bwd"},
+        "untimed_before_warmup": {"settle_s": args.settle_s, "steps": settle_steps,
+                                  "why": "the same step repeated until the clocks have settled, so that a short "
+                                         "run reads like a long one; not part of the timed region"},
         "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
         "ms_per_step_spread": f"median and min over blocks of {block} consecutive steps of the timed region (HIP events)",
         "non_pad_tokens_per_s": nonpad / (elapsed / args.steps),
