@@ -178,14 +178,14 @@ def settle(fn, seconds):
     return n
 
 
-def breakeven(steps, warmup):
+def breakeven(steps, warmup, lengths=(64, 128, 256, 384, 512, 768, 1024)):
     """Section 3.1 uses the faster of two equivalent implementations per sequence length: times
     both here on tables shaped like configuration 2 (B=32, H=12, 4 columns, short cells)."""
     import torch
     from paper_2109_04312_amd import mate, synth
     torch.cuda.set_device(0)
     B, H, rows = 32, 12, []
-    for N in (64, 128, 256, 384, 512, 768, 1024):
+    for N in lengths:
         rng = np.random.default_rng(synth.BASE_SEED + N)
         G, C = max(4, N // 16), 4
         R = max(2, int((N - G) * 0.85 / (C * 2)))
@@ -225,8 +225,8 @@ def breakeven(steps, warmup):
             t[name] = (time.perf_counter() - t0) / steps * 1e6
         rows.append({"N": N, "segment_us": round(t["segment"], 1), "dense_us": round(t["dense"], 1),
                      "faster": min(t, key=t.get)})
-    print(json.dumps({"breakeven": rows, "B": B, "H": H, "dtype": "bf16", "steps": steps,
-                      "step": "segment: build + fwd + bwd; dense: fwd + bwd"}))
+    return {"breakeven": rows, "B": B, "H": H, "dtype": "bf16", "steps": steps,
+            "step": "segment: build + fwd + bwd; dense: fwd + bwd"}
 
 
 def projections(cfg, steps, warmup):
@@ -307,7 +307,7 @@ def projections(cfg, steps, warmup):
            "us_forward_wall": both * 1e6, "us_backward_wall": both_bwd * 1e6, "steps": steps,
            "backward_wall_includes": "weight transposes and pad masks (preparation kernel), partial-sum finalize kernels",
            "flop_convention": "2 * non-pad tokens * K * F per product (pad rows are not algorithmic work)"}
-    print(json.dumps(out))
+    return out
 
 
 def main():
@@ -322,6 +322,9 @@ def main():
     ap.add_argument("--bucketed", default=None, metavar="G,R",
                     help="bucketed mode of Section 3.1 (the published models use 116,42)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the short runs of the other modes (bucketed tables, projections, break-even) "
+                         "that the default line carries under `extras`")
     ap.add_argument("--plain", action="store_true",
                     help="for profiler runs: the warm-up, the timed steps and the per-kernel event pass of the "
                          "chosen configuration, every launch the same shape (no per-head-kind runs, no peak "
@@ -360,11 +363,11 @@ def main():
         return
 
     if args.breakeven:
-        breakeven(args.steps, args.warmup)
+        print(json.dumps(breakeven(args.steps, args.warmup)))
         return
 
     if args.projections:
-        projections(args.config, args.steps, args.warmup)
+        print(json.dumps(projections(args.config, args.steps, args.warmup)))
         return
 
     w = synth.make_config(args.config)
@@ -608,6 +611,36 @@ def main():
                             "algorithmic_GBps": 30.0 * tokens / t_build / 1e9,
                             "frac_hbm": 30.0 * tokens / t_build / 1e9 / PEAK_HBM_GBS},
     }
+    if not args.no_extras and not bucketed and args.config == 4:
+        # the other measured modes in short form, so that one default run shows them all
+        # (`--bucketed`, `--projections` and `--breakeven` give the full versions)
+        def ms_of(fn, n=50):
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / n
+
+        def bucketed_step():
+            mate.build_segments(row, col, flg, out=seg, bucketed=(116, 42))
+            mate.attn_fwd(q, k, v, seg, hk, w.scale, out=out, lse=lse, ws=ws_f)
+            mate.attn_bwd(q, k, v, out, lse, do, seg, hk, w.scale, dq=dq, dk=dk, dv=dv, ws=ws_b)
+
+        pj = projections(args.config, 30, 5)
+        res["extras"] = {
+            "bucketed_G116_R42": {"ms_per_step": ms_of(bucketed_step),
+                                  "useful_pairs": int(sum(useful_pairs_per_view(st, (116, 42))[b, int(hk[h])]
+                                                          for b in range(B) for h in range(H))),
+                                  "step": "mate_build_segments_bucketed + mate_attn_fwd + mate_attn_bwd, same batch"},
+            "projections": {"us_and_frac_of_bf16_peak": {n: [round(v["median_us"], 1), round(v["frac_of_bf16_mfma_peak"], 3)]
+                                                         for n, v in pj["projections"].items()},
+                            "shape": f"{B * N} tokens ({pj['non_pad_tokens']} non-pad) x {pj['E']} -> 3 x {pj['E']} and "
+                                     f"{pj['E']} -> {pj['E']}, flop counted on non-pad tokens"},
+            "breakeven": breakeven(50, 10, lengths=(128, 256, 384, 512)),
+        }
     if not args.no_cpu_baseline and w.do is not None:
         # equal numbers of row and column heads, every sequence: about 10-30 s of CPU work
         rows_h = [h for h in range(H) if hk[h] == 0][:2]
