@@ -166,3 +166,39 @@ def test_bench_pair_count_matches_the_oracle():
                 for v, kind in enumerate((synth.HEAD_ROW, synth.HEAD_COL)):
                     want = orc.useful_pairs(st.row_ids[b], st.col_ids[b], st.flags[b], kind, bucketed=mode)
                     assert got[b, v] == want, (scatter, mode, b, v)
+
+
+def test_bench_reads_the_tracked_traffic_summary(tmp_path):
+    """roofline.traffic comes from the tracked counter summary of the workload: the summary parses,
+    names the three attention kernels with plausible byte counts (at least the outputs each must
+    write: 26.3 MB per tensor on the headline batch), and --summarize-pmc turns profiler csv
+    files into the same lines."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module2", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    table, digest = bench.read_traffic("cfg4_B2_N8192_H16")
+    assert digest and len(digest) == 16
+    per_tensor = 128 * 12853 * 16
+    for kernel, tensors_written in (("fwd_mfma_kernel", 1), ("bwd_dq_mfma_kernel", 1), ("bwd_dkv_mfma_kernel", 2)):
+        assert table[kernel]["write_bytes"] >= tensors_written * per_tensor
+        assert table[kernel]["fetch_bytes"] >= 3 * per_tensor
+        assert table[kernel]["fetch_bytes"] + table[kernel]["write_bytes"] < 40 * per_tensor
+    # the csv -> summary direction, on a two-dispatch file written here
+    for name, counter, values in (("f", "FETCH_SIZE", (100.0, 300.0)), ("w", "WRITE_SIZE", (50.0, 70.0))):
+        d = tmp_path / name
+        d.mkdir()
+        with open(d / "p_counter_collection.csv", "w") as fh:
+            fh.write("Dispatch_Id,Kernel_Name,Counter_Name,Counter_Value\n")
+            for i, v in enumerate(values):
+                # a dispatch reports one row per shader engine / XCD: they add up
+                fh.write(f"{i},mate::(anonymous namespace)::fwd_mfma_kernel(mate::AttnArgs),{counter},{v / 2}\n")
+                fh.write(f"{i},mate::(anonymous namespace)::fwd_mfma_kernel(mate::AttnArgs),{counter},{v / 2}\n")
+    import contextlib
+    import io
+    buf = io.StringIO()
+    with contextlib.redirect_stdout(buf):
+        bench.summarize_pmc(str(tmp_path / "f"), str(tmp_path / "w"))
+    lines = buf.getvalue().split("\n")
+    assert lines[0] == "sources " + bench.sources_digest()
+    assert "counter fwd_mfma_kernel 200 60" in lines
