@@ -429,31 +429,46 @@ def main():
                "attn_bwd_dq": mate.MATE_KERNEL_BWD_DQ, "attn_bwd_dkv": mate.MATE_KERNEL_BWD_DKV}
     per_kernel = max(10, args.steps // len(kernels))
     pairs_ev = {name: [(new_event(), new_event()) for _ in range(per_kernel)] for name in kernels}
+    # An event pair with NOTHING between its two records reads about 5 us on this hardware (what the
+    # command processor spends on the two event packets), and a pair around a kernel reads the
+    # kernel plus that.  One empty pair per profiled step, recorded on the same stream between two
+    # steps, measures it; it is subtracted from every bracket.
+    empty_ev = [(new_event(), new_event()) for _ in range(per_kernel * len(kernels))]
+    stream = C.c_void_p(mate._stream())
     t1 = time.perf_counter()
     for i in range(per_kernel):
-        for name, kid in kernels.items():
+        for j, (name, kid) in enumerate(kernels.items()):
             e0, e1 = pairs_ev[name][i]
             assert mate.mate_profile_kernel(kid, e0, e1) == 0
             step()
+            a0, a1 = empty_ev[i * len(kernels) + j]
+            assert hip.hipEventRecord(a0, stream) == 0 and hip.hipEventRecord(a1, stream) == 0
     torch.cuda.synchronize()
     ms_per_step_pass2 = 1e3 * (time.perf_counter() - t1) / (per_kernel * len(kernels))
-    kernel_s, kernel_median_s, kernel_min_s = {}, {}, {}
+
+    def elapsed_s(e0, e1):
+        ms = C.c_float()
+        assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
+        return ms.value * 1e-3
+
+    empties = sorted(elapsed_s(a0, a1) for a0, a1 in empty_ev)
+    bracket_s = empties[len(empties) // 2]
+    kernel_s, kernel_median_s, kernel_min_s, kernel_raw_s = {}, {}, {}, {}
     for name in kernels:
-        samples = []
-        for e0, e1 in pairs_ev[name]:
-            ms = C.c_float()
-            assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
-            samples.append(ms.value * 1e-3)
-        samples.sort()
-        kernel_s[name] = sum(samples) / len(samples)
-        kernel_median_s[name] = samples[len(samples) // 2]
-        kernel_min_s[name] = samples[0]
+        samples = sorted(elapsed_s(e0, e1) for e0, e1 in pairs_ev[name])
+        kernel_raw_s[name] = sum(samples) / len(samples)
+        kernel_s[name] = kernel_raw_s[name] - bracket_s
+        kernel_median_s[name] = samples[len(samples) // 2] - bracket_s
+        kernel_min_s[name] = samples[0] - bracket_s
     if args.plain:
         print(json.dumps({"plain": True, "workload": w.name, "steps": args.steps, "settle_steps": settle_steps,
                           "ms_per_step": ms_per_step,
                           "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+                          "event_bracket_overhead_us": 1e6 * bracket_s,
                           "kernel_us_hip_events": {n: {"avg": 1e6 * kernel_s[n], "median": 1e6 * kernel_median_s[n],
-                                                       "min": 1e6 * kernel_min_s[n], "launches": per_kernel}
+                                                       "min": 1e6 * kernel_min_s[n],
+                                                       "avg_before_subtracting_the_bracket": 1e6 * kernel_raw_s[n],
+                                                       "launches": per_kernel}
                                                    for n in kernels}}))
         return
     t_build, t_fwd = kernel_s["build_segments"], kernel_s["attn_fwd"]
@@ -590,6 +605,12 @@ def main():
         "useful_tflops_attn_only": 14 * D * pairs / t_attn / 1e12,
         "tokens_per_s_attn_only": tokens / t_attn,
         "kernel_ms": {k: v * 1e3 for k, v in kernel_s.items()},
+        "kernel_ms_events_before_subtracting_the_bracket": {k: v * 1e3 for k, v in kernel_raw_s.items()},
+        "event_bracket_overhead_us": {"value": bracket_s * 1e6,
+                                      "what": "median of event pairs with nothing between their two records, one "
+                                              "per profiled step on the same stream; subtracted from every "
+                                              "per-kernel bracket, so that kernel_ms is the kernel alone (what a "
+                                              "kernel trace shows)"},
         "kernel_ms_median": {k: v * 1e3 for k, v in kernel_median_s.items()},
         "kernel_ms_min": {k: v * 1e3 for k, v in kernel_min_s.items()},
         "ms_per_step_event_pass": ms_per_step_pass2,
