@@ -277,6 +277,7 @@ def projections(cfg, steps, warmup):
         return (time.perf_counter() - t0) / steps
 
     settle(step, 0.3)
+    stream = C.c_void_p(mate._stream())
     both, both_bwd = wall(step), wall(step_bwd)
     res = {}
     for name, kid, fn in (("qkv_project", mate.MATE_KERNEL_QKV_PROJECT, step),
@@ -286,17 +287,23 @@ def projections(cfg, steps, warmup):
                           ("out_project_dgrad", mate.MATE_KERNEL_OUT_PROJECT_DGRAD, step_bwd),
                           ("out_project_wgrad", mate.MATE_KERNEL_OUT_PROJECT_WGRAD, step_bwd)):
         evs = [(new_event(), new_event()) for _ in range(steps)]
-        for e0, e1 in evs:
+        empty = [(new_event(), new_event()) for _ in range(steps)]
+        for (e0, e1), (a0, a1) in zip(evs, empty):
             assert mate.mate_profile_kernel(kid, e0, e1) == 0
             fn()
+            # an event pair with nothing in it: what a bracket reads beyond the kernel (see main())
+            assert hip.hipEventRecord(a0, stream) == 0 and hip.hipEventRecord(a1, stream) == 0
         torch.cuda.synchronize()
-        samples = []
-        for e0, e1 in evs:
-            ms = C.c_float()
-            assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
-            samples.append(ms.value * 1e-3)
-        samples.sort()
-        res[name] = samples[len(samples) // 2]
+
+        def median_s(pairs):
+            out = []
+            for e0, e1 in pairs:
+                ms = C.c_float()
+                assert hip.hipEventElapsedTime(C.byref(ms), e0, e1) == 0
+                out.append(ms.value * 1e-3)
+            return sorted(out)[len(out) // 2]
+
+        res[name] = median_s(evs) - median_s(empty)
     nonpad = int((st.flags != synth.TOK_PAD).sum())
     big, small = 2.0 * nonpad * E * 3 * E, 2.0 * nonpad * E * E
     flop = {"qkv_project": big, "out_project": small, "qkv_project_dgrad": big, "qkv_project_wgrad": big,
@@ -306,7 +313,9 @@ def projections(cfg, steps, warmup):
            "workload": w.name, "B": B, "N": N, "H": H, "E": E, "non_pad_tokens": nonpad, "dtype": "bf16",
            "us_forward_wall": both * 1e6, "us_backward_wall": both_bwd * 1e6, "steps": steps,
            "backward_wall_includes": "weight transposes and pad masks (preparation kernel), partial-sum finalize kernels",
-           "flop_convention": "2 * non-pad tokens * K * F per product (pad rows are not algorithmic work)"}
+           "flop_convention": "2 * non-pad tokens * K * F per product (pad rows are not algorithmic work)",
+           "timing": "median of HIP event brackets recorded by the library around each launch, minus the median "
+                     "of event pairs with nothing between their records"}
     return out
 
 
